@@ -5,7 +5,13 @@ A "step" is one gss_step (all hops: read snapshot, refresh, draw, dedupe/relabel
 batch of seeds; FCR full refreshes fall inside the timed region.  Inputs (CSR, seeds) are resident in HBM
 before the clock starts.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2_medium_fcr] [--others]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4_large_shared] [--only]
+
+The line's headline is --workload (default: the largest configuration, cfg4_large_shared); the other four
+configurations are measured in the same run and reported under "other_workloads" (--only skips them).
+Per workload: the fill/drain-inclusive time of exactly K steps (ms_per_step, value), the steady-state time per step
+with the pipeline full at both ends of the window (steady_ms_per_step), the time of one blocking gss_step alone
+(blocking_step_ms), the roofline figures of the dominant kernel and the oracle on one host core.
 """
 from __future__ import annotations
 
@@ -23,29 +29,37 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
 
 
-def algorithmic_bytes(w, counts, indptr_bytes):
-    """Bytes the method must move for the given totals (the per-unit figures of the byte model):
-    per frontier node 4 (id) + 4k (row) [+ OTF/shared: 2 indptr words + 8 n_new (+ 8 stamp)];
-    per sampled edge 4 (pick write) + 16 (table insert)   sample phase
-                     4 (pick read) + 8 (table probe)       mark phase
-                     8 (COO write), per new source 4       emit phase.
-    FBL: no row; per node 4 + 2 indptr words, and 4 more per edge (the adjacency entry of the draw).
-    OTF fetch: the row and 2 indptr words per node, 4 more for the fetched share of the edges."""
-    nodes, edges, uniq = counts
+def byte_model(w, indptr_bytes):
+    """Algorithmic bytes per unit - what the method must move, sector granularity not counted:
+      per frontier node and hop  4 (id) + 4k (cached row)
+                                 + per-visit refresh (OTF, shared OTF): 2 indptr words + 8 n_new (n_new adjacency
+                                   reads and n_new row writes), + 8 (stamp read / write) with the shared table
+      per sampled edge           32 = 4 (pick write) + 4 (pick read) + 16 (dedupe insert: 8 read + 8 atomic) + 8 (COO)
+      per new source node        8 = 4 (src_nodes write) + 4 (read as next frontier)
+    FBL keeps no row: per node 4 + 2 indptr words, and 4 more per edge (the adjacency entry of the draw).
+    OTF fetch: the row and 2 indptr words per node, 4 more for the fetched share of the edges.
+    The implementation's own extra traffic (the mark phase probes the dedupe word again: 8 per edge) is returned
+    separately and never enters `achieved`."""
     k = w.k
     otf = w.mode in (1, 2)
     n_new = int(w.refresh_fraction * k + 1e-9) if otf else 0
     per_node = 4 + 4 * k
-    per_edge = 20 + 12 + 8
+    per_edge = 32
     if otf:
         per_node += 2 * indptr_bytes + 8 * n_new + (8 if w.mode == 2 else 0)
     if w.mode == 3:
         per_node = 4 + 2 * indptr_bytes
         per_edge += 4
-    if w.mode == 5:   # OTF fetch: the row, the adjacency bounds, and delta of the edges read from the adjacency
+    if w.mode == 5:
         per_node += 2 * indptr_bytes
         per_edge += 4 * w.refresh_fraction
-    return nodes * per_node + edges * per_edge + uniq * 4
+    return dict(per_node=per_node, per_edge=per_edge, per_unique=8, impl_extra_per_edge=8)
+
+
+def algorithmic_bytes(w, counts, indptr_bytes):
+    nodes, edges, uniq = counts
+    m = byte_model(w, indptr_bytes)
+    return nodes * m["per_node"] + edges * m["per_edge"] + uniq * m["per_unique"]
 
 
 def cpu_model():
@@ -73,101 +87,170 @@ def fill_full_bytes(w, graph):
     return total
 
 
-def run_gpu(w, graph, steps, warmup, profile_steps):
+def make_sampler(w, dev_rels, graph):
+    from paper_2406_17918_amd import gss
+    return gss.Sampler(graph.num_nodes, dev_rels, k=w.k, mode=w.mode, num_layers=len(w.fanouts),
+                       refresh_fraction=w.refresh_fraction, refresh_period=w.refresh_period, rng_seed=w.rng_seed,
+                       degree_threshold=getattr(w, "degree_threshold", -1))
+
+
+def run_gpu(w, graph, steps, warmup, profile_steps, steady_steps=0, blocking_steps=0):
+    """Timed passes over consecutive step numbers of ONE sampler:
+      1. `warmup` untimed steps, then exactly `steps` steps between two device synchronisations (the pipeline fills
+         and drains inside the timed region);
+      2. steady state: 2 * depth + `steady_steps` steps in one uninterrupted stream; the window runs from the
+         completion of the step after which the pipeline has been full for `depth` steps to the completion of the
+         step `steady_steps` later (host clock at the return of gss_step_wait);
+      3. `profile_steps` steps with HIP-event brackets attached to every kernel dispatch (on the library's stream);
+      4. `blocking_steps` blocking gss_step calls, nothing else in flight: the latency of one step alone."""
     import torch
     from paper_2406_17918_amd import gss
     dev_rels = gss.upload_graph(graph)
-    n_total = warmup + steps + profile_steps
+    s = make_sampler(w, dev_rels, graph)
+    depth = s.pipeline_depth
+    n_steady = (2 * depth + steady_steps) if steady_steps else 0
+    n_total = warmup + steps + n_steady + profile_steps + blocking_steps
     seeds = [torch.from_numpy(w.seeds(graph, i)).cuda() for i in range(n_total)]
-    s = gss.Sampler(graph.num_nodes, dev_rels, k=w.k, mode=w.mode, num_layers=len(w.fanouts),
-                    refresh_fraction=w.refresh_fraction, refresh_period=w.refresh_period, rng_seed=w.rng_seed,
-                    degree_threshold=getattr(w, "degree_threshold", -1))
     cache_bytes = s.cache_bytes()
-    def run_steps(first, last):
+
+    def run_steps(first, last, on_done=None):
         # up to gss_pipeline_depth() steps are enqueued before the oldest is collected, so the GPU never waits for the host
         edges = 0
         inflight = 0
         for i in range(first, last):
             s.step_async(seeds[i], w.fanouts, i, w.seed_type)
             inflight += 1
-            if inflight == s.pipeline_depth:
-                edges += s.step_wait_raw().total_edges
+            if inflight == depth:
+                b = s.step_wait_raw()
+                edges += b.total_edges
                 inflight -= 1
+                if on_done:
+                    on_done(b)
         while inflight:
-            edges += s.step_wait_raw().total_edges
+            b = s.step_wait_raw()
+            edges += b.total_edges
             inflight -= 1
+            if on_done:
+                on_done(b)
         return edges
 
-    run_steps(0, warmup)            # untimed, same launch configuration as the timed region
+    pos = 0
+    run_steps(pos, pos + warmup)            # untimed, same launch configuration as the timed region
+    pos += warmup
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    edges = run_steps(warmup, warmup + steps)
+    edges = run_steps(pos, pos + steps)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    pos += steps
+    res = dict(seconds=dt, edges=int(edges), prof={}, prof_counts=(0, 0, 0), prof_refreshes=0, prof_steps=0,
+               cache_bytes=cache_bytes, depth=depth, steady=None, blocking=None)
 
-    # second pass over the following steps, in the same launch configuration, with HIP-event brackets around every
-    # kernel launch (on the stream the kernel is launched on)
-    if profile_steps == 0:
-        s.close()
-        return dict(seconds=dt, edges=int(edges), prof={}, prof_counts=(0, 0, 0), prof_refreshes=0, prof_steps=0,
-                    cache_bytes=cache_bytes)
-    s.profile_enable(True)
-    T, R = len(graph.num_nodes), len(graph.relations)
-    nodes = pe = uniq = 0
-    refreshes = 0
+    if n_steady:
+        stamps, sedges = [], []
 
-    def account(b):
-        nonlocal nodes, pe, uniq
-        pe += b.total_edges
-        for l in range(b.num_layers):
-            for t in range(T):
-                nd = b.nodes[l * T + t]
-                uniq += nd.num_src - nd.num_dst
-            for r in range(R):
-                nodes += b.nodes[l * T + graph.relations[r].dst_type].num_dst
+        def done(b):
+            stamps.append(time.perf_counter())
+            sedges.append(b.total_edges)
+        run_steps(pos, pos + n_steady, done)
+        torch.cuda.synchronize()
+        pos += n_steady
+        lo, hi = depth - 1, depth - 1 + steady_steps     # completions of steps lo and hi: full pipeline in between
+        res["steady"] = dict(seconds=stamps[hi] - stamps[lo], steps=steady_steps, edges=int(sum(sedges[lo + 1:hi + 1])))
 
-    inflight = 0
-    for i in range(warmup + steps, n_total):
-        s.step_async(seeds[i], w.fanouts, i, w.seed_type)
-        inflight += 1
-        if inflight == s.pipeline_depth:
-            account(s.step_wait_raw())
-            inflight -= 1
-        if w.mode in (0, 4, 6) and i % w.refresh_period == 0 and i > 0:
-            refreshes += 1
-    while inflight:
-        account(s.step_wait_raw())
-        inflight -= 1
-    prof = s.profile_read()
-    s.profile_enable(False)
+    if profile_steps:
+        s.profile_enable(True)
+        T, R = len(graph.num_nodes), len(graph.relations)
+        nodes = pe = uniq = 0
+
+        def account(b):
+            nonlocal nodes, pe, uniq
+            pe += b.total_edges
+            for l in range(b.num_layers):
+                for t in range(T):
+                    nd = b.nodes[l * T + t]
+                    uniq += nd.num_src - nd.num_dst
+                for r in range(R):
+                    nodes += b.nodes[l * T + graph.relations[r].dst_type].num_dst
+        run_steps(pos, pos + profile_steps, account)
+        refreshes = 0
+        if w.mode in (0, 4, 6):
+            refreshes = sum(1 for i in range(pos, pos + profile_steps) if i % w.refresh_period == 0 and i > 0)
+        pos += profile_steps
+        res.update(prof=s.profile_read(), prof_counts=(nodes, pe, uniq), prof_refreshes=refreshes, prof_steps=profile_steps)
+        s.profile_enable(False)
+
+    if blocking_steps:
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(pos, pos + blocking_steps):
+            s.step_raw(seeds[i], w.fanouts, i, w.seed_type)
+        res["blocking"] = dict(seconds=time.perf_counter() - t0, steps=blocking_steps)
+        pos += blocking_steps
     s.close()
-    return dict(seconds=dt, edges=int(edges), prof=prof, prof_counts=(nodes, pe, uniq), prof_refreshes=refreshes,
-                prof_steps=profile_steps, cache_bytes=cache_bytes)
+    return res
 
 
-def run_oracle(w, graph, steps, warmup):
+def run_oracle(w, graph, first_step, max_steps, budget_s):
+    """The oracle as it stands, one thread, on the steps first_step, first_step + 1, ... of the same workload (the
+    steps before them are run untimed, so that its cache is in the state the GPU's timed region starts from), until
+    `max_steps` steps or `budget_s` seconds.  It counts its own edges."""
     from oracle import gsso
+    import ctypes as C
     rels = [gsso.Relation(r.src_type, r.dst_type, r.indptr, r.indices) for r in graph.relations]
     o = gsso.Sampler(graph.num_nodes, rels, k=w.k, mode=w.mode, num_layers=len(w.fanouts),
-                     refresh_fraction=w.refresh_fraction, refresh_period=w.refresh_period, rng_seed=w.rng_seed)
+                     refresh_fraction=w.refresh_fraction, refresh_period=w.refresh_period, rng_seed=w.rng_seed,
+                     degree_threshold=getattr(w, "degree_threshold", -1))
     lib = gsso.lib()
-    import ctypes as C
-    seeds = [np.ascontiguousarray(w.seeds(graph, i)) for i in range(warmup + steps)]
     fo = (C.c_int32 * len(w.fanouts))(*w.fanouts)
     p32 = C.POINTER(C.c_int32)
-    for i in range(warmup):
-        assert lib.gsso_step(o._h, seeds[i].ctypes.data_as(p32), len(seeds[i]), w.seed_type, fo, len(w.fanouts), i) == 0
-    edges = 0
-    t0 = time.perf_counter()
-    for i in range(warmup, warmup + steps):
-        assert lib.gsso_step(o._h, seeds[i].ctypes.data_as(p32), len(seeds[i]), w.seed_type, fo, len(w.fanouts), i) == 0
-    dt = time.perf_counter() - t0
-    # the edge total is taken from the GPU run: parity makes the two identical
+    L, R = len(w.fanouts), len(graph.relations)
+    ne, pa, pb = C.c_int32(), p32(), p32()
+
+    def one(i):
+        sd = np.ascontiguousarray(w.seeds(graph, i))
+        t0 = time.perf_counter()
+        st = lib.gsso_step(o._h, sd.ctypes.data_as(p32), len(sd), w.seed_type, fo, L, i)
+        dt = time.perf_counter() - t0
+        assert st == 0
+        e = 0
+        for l in range(L):
+            for r in range(R):
+                lib.gsso_block_edges(o._h, l, r, C.byref(ne), C.byref(pa), C.byref(pb))
+                e += ne.value
+        return dt, e
+
+    for i in range(first_step):
+        one(i)
+    seconds, edges, n = 0.0, 0, 0
+    while n < max_steps and (seconds < budget_s or n < 2):
+        dt, e = one(first_step + n)
+        seconds += dt
+        edges += e
+        n += 1
     o.close()
-    return dt
+    return dict(seconds=seconds, edges=edges, steps=n)
 
 
-def roofline_of(w, graph, res):
+_TRAFFIC = None
+
+
+def recorded_traffic(workload, kernel, lib_version):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, each scaled by a plain copy of
+    known size) - a RECORDED figure, kept in profiles/traffic.json together with the version string of the library
+    it was measured on; None when the library has changed since."""
+    global _TRAFFIC
+    if _TRAFFIC is None:
+        try:
+            _TRAFFIC = json.load(open(os.path.join(ROOT, "profiles", "traffic.json")))
+        except Exception:
+            _TRAFFIC = {}
+    if _TRAFFIC.get("library_version") != lib_version:
+        return None
+    return _TRAFFIC.get("bytes_per_launch", {}).get(workload, {}).get(kernel)
+
+
+def roofline_of(w, graph, res, lib_version):
     """step_tick is the kernel every phase of every step runs in (one launch carries one phase of each step in
     flight); fill_full is the FCR refresh.  Algorithmic bytes per launch = the bytes of the profiled steps divided by
     the launches that processed them."""
@@ -186,19 +269,72 @@ def roofline_of(w, graph, res):
                                 gbs=(total_bytes / launches) / (1e-3 * ms / launches) / 1e9 if ms > 0 else 0.0)
     dom = max(per_kernel, key=lambda n: per_kernel[n]["ms_total"])
     d = per_kernel[dom]
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get(w.name, {}).get(dom)
-        except Exception:
-            traffic = None
+    m = byte_model(w, indptr_bytes)
     roof = dict(bound="hbm", kernel=dom, achieved=round(d["gbs"], 3), peak=HBM_PEAK_GBS, unit="GB/s",
-                frac=round(d["gbs"] / HBM_PEAK_GBS, 6), traffic=traffic,
-                avg_launch_us=round(d["avg_us"], 3), alg_bytes_per_launch=round(d["alg_bytes_per_launch"], 1))
+                frac=round(d["gbs"] / HBM_PEAK_GBS, 6),
+                traffic=recorded_traffic(w.name, dom, lib_version),
+                traffic_kind="recorded: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised in profiles/ (null: none for this library version)",
+                avg_launch_us=round(d["avg_us"], 3), alg_bytes_per_launch=round(d["alg_bytes_per_launch"], 1),
+                launches_per_step=round(d["launches"] / max(res["prof_steps"], 1), 3),
+                byte_model=m,
+                impl_extra_bytes_per_launch=round(edges * m["impl_extra_per_edge"] / d["launches"], 1) if dom == "step_tick" else 0)
     kernels = {n: dict(avg_us=round(v["avg_us"], 3), launches=v["launches"], alg_gbs=round(v["gbs"], 3))
                for n, v in per_kernel.items()}
     return roof, kernels
+
+
+MODE_NAMES = ["FCR", "OTF", "SHARED_OTF", "FBL", "SHARED_FCR", "OTF_FETCH", "OTF_LAYER"]
+
+
+def measure_workload(w, graph, steps, warmup, cpu_budget_s, lib_version):
+    """Every figure of one workload (see run_gpu); the oracle leg is skipped when cpu_budget_s == 0."""
+    steady_steps = max(steps, 200)
+    res = run_gpu(w, graph, steps, warmup, profile_steps=max(steps, 100), steady_steps=steady_steps, blocking_steps=20)
+    roof, kernels = roofline_of(w, graph, res, lib_version)
+    indptr_bytes = graph.relations[0].indptr.itemsize
+    step_bytes = algorithmic_bytes(w, res["prof_counts"], indptr_bytes) / max(res["prof_steps"], 1)
+    st = res["steady"]
+    steady_ms = 1e3 * st["seconds"] / st["steps"]
+    cpu = None
+    if cpu_budget_s > 0:
+        o = run_oracle(w, graph, warmup, 5000, cpu_budget_s)
+        cpu = dict(value=round(o["edges"] / o["seconds"], 1), unit="sampled edges/s", cores=1, kind="oracle",
+                   sample=f"steps {warmup} .. {warmup + o['steps'] - 1} of {w.name} (the step numbers the timed region starts at; as many as "
+                          f"fit the time bound) after the same {warmup} warmup steps "
+                          f"({o['seconds']:.2f} s of single-thread CPU work, {o['edges']} edges counted by the oracle itself; "
+                          f"cache initialisation excluded)",
+                   host_cpus=os.cpu_count(), host_cpu_model=cpu_model())
+    return {
+        "value": round(res["edges"] / res["seconds"], 1), "unit": "sampled edges/s",
+        "ms_per_step": round(1e3 * res["seconds"] / steps, 5),
+        "steady_ms_per_step": round(steady_ms, 5),
+        "steady_value": round(st["edges"] / st["seconds"], 1),
+        "steady_window_steps": st["steps"],
+        "blocking_step_ms": round(1e3 * res["blocking"]["seconds"] / res["blocking"]["steps"], 5),
+        "pipeline_depth": res["depth"],
+        "config": {"workload": w.name, "graph": graph.meta, "nodes": graph.num_nodes,
+                   "csr_entries": [int(len(r.indices)) for r in graph.relations], "batch": w.batch,
+                   "fanouts": w.fanouts, "k": w.k, "mode": MODE_NAMES[w.mode],
+                   "refresh_fraction": w.refresh_fraction, "refresh_period": w.refresh_period,
+                   "stands_in_for": w.stands_in_for},
+        "seeds_per_s": round(w.batch * steps / res["seconds"], 1),
+        "steady_seeds_per_s": round(w.batch / (1e-3 * steady_ms), 1),
+        "edges_per_step": round(res["edges"] / steps, 1),
+        # algorithmic bytes over the kernel's own time, and over the wall time of a steady-state step (the gap is
+        # launch latency and idle time between launches)
+        "hbm_pct_of_peak": round(100.0 * roof["frac"], 4),
+        "hbm_pct_of_peak_wall": round(100.0 * step_bytes / (1e-3 * steady_ms) / 1e9 / HBM_PEAK_GBS, 4),
+        "alg_bytes_per_step": round(step_bytes, 1),
+        "cache_bytes": res["cache_bytes"],
+        "cache_bytes_logical": logical_cache_bytes(w, graph),
+        "roofline": roof, "kernels": kernels, "cpu_baseline": cpu,
+    }
+
+
+def logical_cache_bytes(w, graph):
+    """The [tables, N, k] int32 cells of the cache as the paper counts it (one table set, no row padding)."""
+    ntab = 0 if w.mode == 3 else (1 if w.mode in (2, 4) else len(w.fanouts))
+    return int(sum(4 * w.k * ntab * (len(r.indptr) - 1) for r in graph.relations))
 
 
 def paper_table(graph_name, steps, warmup):
@@ -312,11 +448,14 @@ def gather_bench(w, graph, steps, warmup, dim):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--workload", default="cfg2_medium_fcr")
-    ap.add_argument("--others", action="store_true", help="also time the other workloads (adds ~1-2 min of graph generation)")
+    ap.add_argument("--workload", default="cfg4_large_shared",
+                    help="the headline workload of the line (default: the largest single-GPU configuration)")
+    ap.add_argument("--only", action="store_true", help="measure --workload alone (the default line also carries the other four)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="bound of the oracle's timed work on the headline workload (the others get a third of it each)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="first run a plain 256 MiB device copy (a kernel of known traffic, to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -345,66 +484,49 @@ def main():
         del src, dst
 
     if a.paper_table:
-        paper_table(a.workload, a.steps, a.warmup)
+        paper_table(a.workload if a.workload != "cfg4_large_shared" else "cfg2_medium_fcr", a.steps, a.warmup)
         return
 
     if a.degree_split_table:
         degree_split_table(a.workload, a.steps, a.warmup)
         return
 
-    from paper_2406_17918_amd import synth
+    from paper_2406_17918_amd import synth, gss
+    lib_version = gss.load_library().gss_version().decode()
     w = synth.WORKLOADS[a.workload]
     if a.batch > 0:
         import copy
         w = copy.copy(w)
         w.batch = a.batch
-    graph = w.make_graph()
+    graphs = {}
+
+    def graph_of(name):       # cfg3 and cfg4 run on the same graph: generated once
+        key = "large" if name in ("cfg3_large_otf", "cfg4_large_shared") else name
+        if key not in graphs:
+            graphs[key] = synth.WORKLOADS[name].make_graph()
+        return graphs[key]
+
+    graph = graph_of(w.name)
     if a.gather:
         gather_bench(w, graph, min(a.steps, 100), min(a.warmup, 10), a.feature_dim)
         return
-    res = run_gpu(w, graph, a.steps, a.warmup, profile_steps=a.steps)
-    value = res["edges"] / res["seconds"]
-    roof, kernels = roofline_of(w, graph, res)
-    step_bytes = algorithmic_bytes(w, res["prof_counts"], graph.relations[0].indptr.itemsize) / max(res["prof_steps"], 1)
-
-    cpu = None
-    if not a.no_cpu_baseline:
-        t = run_oracle(w, graph, a.steps, a.warmup)
-        cpu = dict(value=round(res["edges"] / t, 1), unit="sampled edges/s", cores=1, kind="oracle",
-                   sample=f"the same {a.steps} timed steps of {w.name} after the same {a.warmup} warmup steps "
-                          f"({t:.2f} s of single-thread CPU work; cache initialisation excluded)",
-                   host_cpus=os.cpu_count(), host_cpu_model=cpu_model())
-
+    cpu_s = 0.0 if a.no_cpu_baseline else a.cpu_seconds
+    head = measure_workload(w, graph, a.steps, a.warmup, cpu_s, lib_version)
     out = {
         "metric": "sampled edges/sec per minibatch step (3-hop) + achieved HBM GB/s % of peak",
-        "value": round(value, 1), "unit": "sampled edges/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": round(1e3 * res["seconds"] / a.steps, 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "int32", "data": "synthetic",
-        "config": {"workload": w.name, "graph": graph.meta, "nodes": graph.num_nodes,
-                   "csr_entries": [int(len(r.indices)) for r in graph.relations], "batch": w.batch,
-                   "fanouts": w.fanouts, "k": w.k, "mode": ["FCR", "OTF", "SHARED_OTF", "FBL", "SHARED_FCR", "OTF_FETCH", "OTF_LAYER"][w.mode],
-                   "refresh_fraction": w.refresh_fraction, "refresh_period": w.refresh_period,
-                   "stands_in_for": w.stands_in_for},
-        "seeds_per_s": round(w.batch * a.steps / res["seconds"], 1),
-        "edges_per_step": round(res["edges"] / a.steps, 1),
-        # algorithmic bytes over the kernel's own time, and over the wall time of the steps (the gap is launch latency)
-        "hbm_pct_of_peak": round(100.0 * roof["frac"], 4),
-        "hbm_pct_of_peak_wall": round(100.0 * step_bytes / (res["seconds"] / a.steps) / 1e9 / HBM_PEAK_GBS, 4),
-        "cache_bytes": res["cache_bytes"],
-        "roofline": roof, "kernels": kernels, "cpu_baseline": cpu,
+        "value": head.pop("value"), "unit": head.pop("unit"), "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": head.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int32", "data": "synthetic", "library": lib_version,
     }
-    if a.others:
+    out.update(head)
+    if not a.only and a.batch == 0:
+        key_of = lambda n: "large" if n in ("cfg3_large_otf", "cfg4_large_shared") else n
+        names = [n for n in synth.WORKLOADS if n != w.name]
         others = {}
-        for name, ow in synth.WORKLOADS.items():
-            if name == w.name:
-                continue
-            g2 = ow.make_graph()
-            k2 = 200
-            r2 = run_gpu(ow, g2, k2, 24, profile_steps=k2)
-            rf, _ = roofline_of(ow, g2, r2)
-            others[name] = dict(value=round(r2["edges"] / r2["seconds"], 1), ms_per_step=round(1e3 * r2["seconds"] / k2, 5),
-                                seeds_per_s=round(ow.batch * k2 / r2["seconds"], 1), steps=k2, roofline=rf)
-            del g2
+        for i, name in enumerate(names):
+            for key in [k for k in graphs if k not in {key_of(n) for n in names[i:]}]:
+                del graphs[key]       # host memory: keep only the graphs still to be measured
+            others[name] = measure_workload(synth.WORKLOADS[name], graph_of(name), a.steps, a.warmup, cpu_s / 3.0, lib_version)
         out["other_workloads"] = others
     print(json.dumps(out))
 

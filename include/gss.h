@@ -217,7 +217,8 @@ gss_status gss_cache_bytes(const gss_sampler* s, int64_t* out);
 gss_status gss_gather_rows(const void* table, int64_t num_rows, int64_t row_bytes, const int32_t* ids, int64_t num_ids,
                            void* out, void* hip_stream);
 
-/* Human-readable description of the last error on the handle ("" if none). Never NULL. */
+/* Human-readable description of the last error on the handle ("" if none). Never NULL.
+ * With s == NULL: why the calling thread's last gss_create failed ("" if it did not). */
 const char* gss_last_error(const gss_sampler* s);
 
 /* Kernel timing (measurement aid; off by default).  While enabled, every kernel launch of the handle is

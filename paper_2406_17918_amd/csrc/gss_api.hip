@@ -187,6 +187,9 @@ struct gss_sampler {
 
 namespace {
 
+// Why the last gss_create of this thread failed (gss_last_error(NULL) returns it): there is no handle to ask then.
+thread_local char g_create_err[256] = {0};
+
 gss_status fail(gss_sampler* s, gss_status st, const char* fmt, ...) {
   if (s) {
     va_list ap;
@@ -529,7 +532,7 @@ extern "C" {
 
 const char* gss_version(void) { return "gss 0.2 (gfx950)"; }
 
-const char* gss_last_error(const gss_sampler* s) { return s ? s->err : "null sampler"; }
+const char* gss_last_error(const gss_sampler* s) { return s ? s->err : g_create_err; }
 
 gss_status gss_create(const gss_graph* g, const gss_config* c, gss_sampler** out) {
   if (!out) return GSS_ERR_INVALID_ARG;
@@ -581,8 +584,19 @@ gss_status gss_create(const gss_graph* g, const gss_config* c, gss_sampler** out
   for (int t = 0; t < s->T; ++t) { s->num_nodes[t] = g->num_nodes[t]; s->key_off[t] = off; off += (uint32_t)g->num_nodes[t]; }
   for (int r = 0; r < s->R; ++r) s->rel[r] = g->relations[r];
 
-  auto bail = [&](gss_status st) { destroy_impl(s); return st; };
-  auto hipfail = [&](hipError_t) { return bail(GSS_ERR_DEVICE); };
+  g_create_err[0] = 0;
+  // (the message of the failing call, if it left one on the handle, else the status name)
+  auto bail = [&](gss_status st) {
+    static const char* const names[] = {"ok", "invalid argument", "invalid graph", "invalid seed", "allocation failed",
+                                        "device error", "step order"};
+    snprintf(g_create_err, sizeof g_create_err, "create: %s", s->err[0] ? s->err : names[(int)st]);
+    destroy_impl(s);
+    return st;
+  };
+  auto hipfail = [&](hipError_t err) {
+    if (!s->err[0]) snprintf(s->err, sizeof s->err, "%s", hipGetErrorString(err));
+    return bail(GSS_ERR_DEVICE);
+  };
 
   if (const char* ev = getenv("GSS_SCAN")) s->force_scan_kernel = !strcmp(ev, "kernel");
   if (const char* ev = getenv("GSS_INSERT")) s->insert_policy = !strcmp(ev, "split") ? 1 : !strcmp(ev, "fused") ? 2 : 0;

@@ -75,6 +75,9 @@ def load_library():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} not found: build it with `python -m paper_2406_17918_amd.build` "
                            "(there is no fallback path)")
+    # PyTorch supplies the device memory and the streams: its HIP runtime must be the process's one, so it is loaded
+    # first (a runtime loaded before torch's own copy ends up beside it and sees no device)
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     L.gss_create.argtypes = [C.POINTER(gss_graph), C.POINTER(gss_config), C.POINTER(C.c_void_p)]
     L.gss_create.restype = C.c_int
@@ -224,7 +227,7 @@ class Sampler:
         h = C.c_void_p()
         st = self._lib.gss_create(C.byref(g), C.byref(cfg), C.byref(h))
         if st != GSS_OK:
-            raise GssError(st, "gss_create failed")
+            raise GssError(st, "gss_create failed: " + self._lib.gss_last_error(None).decode())
         self._h = h
         self.pipeline_depth = int(self._lib.gss_pipeline_depth(h))   # steps that may be in flight
         self._blocks = gss_blocks()
