@@ -148,13 +148,33 @@ typedef struct gss_sampler gss_sampler;
 /* StaticSample / Initialize (Alg. 1, Alg. 2): validates the graph, allocates the cache tables
  * ([num_nodes[dst_type], k] int32 per layer and relation, -1 padded) and fills every row with a
  * uniform min(deg,k)-subset of the node's adjacency (step word 0).  Blocks until the fill is done.
- * On error *out is NULL and nothing is leaked.
- * Environment variables read here change how the work is laid out, never what is computed (they exist for tests
- * and measurements): GSS_DEDUPE=direct|hash (dedupe table layout), GSS_FCR_SETS=1..5 (table sets of the
- * epoch-refreshed modes), GSS_DEPTH=1..GSS_MAX_IN_FLIGHT (gss_pipeline_depth), GSS_STEPS_PER_TICK=1|2 (steps a launch
- * starts), GSS_INSERT=split|fused and GSS_SCAN=kernel (which phases a hop is cut into), GSS_TICK_BUILD=dense|plain
- * (which of the step kernel's two register budgets every launch uses). */
+ * On error *out is NULL, nothing is leaked and gss_last_error(NULL) says why.  The library reads no environment
+ * variable. */
 gss_status gss_create(const gss_graph* graph, const gss_config* config, gss_sampler** out);
+
+/* How the work is laid out - never what is computed: every field changes launch shapes, buffer layouts or memory use
+ * only, and results stay bit-identical.  0 in a field = the library's own choice.  For memory budgeting (table_sets,
+ * pipeline_depth), measurements and tests. */
+typedef struct {
+  int32_t dedupe_layout;        /* 1: direct (one 8-byte word per node and step in flight), 2: hashed (open addressing,
+                                   16-byte entries, sized by the batch).  Default: direct up to 8 GiB of words.       */
+  int32_t table_sets;           /* epoch-refreshed modes (FCR, SHARED_FCR, OTF_LAYER): 1..5 sets of tables.  A refresh
+                                   writes a set that no step in flight reads; with one set it waits for them.  Default:
+                                   2 + depth / period sets (3 at least, 5 at most) when they fit 1/8 of the free device
+                                   memory at gss_create, else 3, else 2 (if they fit half of it), else 1.            */
+  int32_t pipeline_depth;       /* 1..GSS_MAX_IN_FLIGHT: value of gss_pipeline_depth().  Default 4 L + 2 (twice that
+                                   where a launch starts two steps).  Every step in flight owns scratch, outputs and
+                                   (direct layout) a dedupe table.                                                    */
+  int32_t steps_per_tick;       /* 1 | 2: steps a launch starts (2 only in modes that never write a table)           */
+  int32_t insert_phase;         /* 1: every hop gets a separate insert phase, 2: none does                           */
+  int32_t scan_phase;           /* 1: every hop gets a separate scan phase                                           */
+  int32_t tick_build;           /* 1: every launch uses the step kernel's 8-workgroups-per-CU build, 2: none does     */
+  uint32_t first_dedupe_version;/* start of each slot's dedupe-table version counter (tests of the wrap-around)       */
+  int32_t reserved[8];          /* must be 0                                                                          */
+} gss_tuning;
+
+/* gss_create with the layout choices of `tuning` (NULL: all defaults, which is what gss_create passes). */
+gss_status gss_create_tuned(const gss_graph* graph, const gss_config* config, const gss_tuning* tuning, gss_sampler** out);
 
 /* SampleBlocks (Alg. 2 / Alg. 3): one minibatch.
  *   seeds      device, [num_seeds] distinct ids of node type seed_type (borrowed for the call)

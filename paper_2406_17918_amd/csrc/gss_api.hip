@@ -153,6 +153,8 @@ struct gss_sampler {
   int64_t cache_bytes = 0;               // tables + row maps + stamps
   int32_t* state_d = nullptr;            // create-time state (graph validation, initial fill)
   int32_t* state_h = nullptr;
+  int32_t* fill_state_d = nullptr;       // error flag of the refreshes computed ahead of time on the fill stream, and its
+  int32_t* fill_state_h = nullptr;       // pinned host copy (copied after every such refresh, checked when its epoch starts)
   int state_words = 0;
   Buf checksum;
   bool use_direct = true;
@@ -160,9 +162,10 @@ struct gss_sampler {
   bool fcr = false;                      // every table is rewritten when floor(step/R) changes (FCR, SHARED_FCR, OTF_LAYER)
   bool layer_partial = false;            // ... by a partial refresh of every row instead of a fill (OTF_LAYER)
   bool otf = false;                      // partial refresh per visit (OTF, SHARED_OTF)
-  bool force_scan_kernel = false;        // GSS_SCAN=kernel: always use the separate scan phase (tests)
-  int insert_policy = 0;                 // 0: large hops get an insert phase; GSS_INSERT=split: all hops, =fused: none (tests)
-  int dense_policy = 0;                  // 0: launches of DENSE_TICK_WGS workgroups and more use the dense build; GSS_TICK_BUILD=dense: all, =plain: none (tests)
+  bool force_scan_kernel = false;        // gss_tuning.scan_phase: always use the separate scan phase
+  int insert_policy = 0;                 // gss_tuning.insert_phase - 0: large and narrow hops get an insert phase; 1: all hops, 2: none
+  int dense_policy = 0;                  // gss_tuning.tick_build - 0: launches of DENSE_TICK_WGS workgroups and more use the dense build; 1: all, 2: none
+  uint32_t first_version = VERSION_FIRST;   // where a slot's dedupe-table version counter starts
   int tick_cap = 1;                      // slices one launch can carry
   RelConst relc_h[GSS_MAX_RELATIONS] = {};   // per relation constants: host copy and device copy
   RelConst* relc_d = nullptr;
@@ -213,12 +216,15 @@ void dev_free(gss_sampler* s, void* p) {
 }
 // grow-only buffer; contents are not preserved.  Only called for a slot whose previous step has
 // been collected, so nothing in flight reads the buffer that is released.
+// When the allocation fails the buffer stays as it was.
 bool ensure(gss_sampler* s, Buf& b, size_t bytes) {
   if (b.bytes >= bytes && b.p) return true;
+  void* p = dev_alloc(s, bytes);
+  if (!p) return false;
   dev_free(s, b.p);
-  b.p = dev_alloc(s, bytes);
-  b.bytes = b.p ? std::max<size_t>(bytes, 16) : 0;
-  return b.p != nullptr;
+  b.p = p;
+  b.bytes = std::max<size_t>(bytes, 16);
+  return true;
 }
 void release(gss_sampler* s, Buf& b) { dev_free(s, b.p); b.p = nullptr; b.bytes = 0; }
 
@@ -473,8 +479,9 @@ gss_status drain(gss_sampler* s) {
 gss_status fill_on_fill_stream(gss_sampler* s, uint32_t stepword, int set) {
   HIP_TRY(s, hipEventRecord(s->fill_go, s->work));
   HIP_TRY(s, hipStreamWaitEvent(s->fill_stream, s->fill_go, 0));
-  gss_status rs = fill_all_tables(s, stepword, s->state_d, s->fill_stream, set, s->cur_set);
+  gss_status rs = fill_all_tables(s, stepword, s->fill_state_d, s->fill_stream, set, s->cur_set);
   if (rs != GSS_OK) { s->poisoned = true; return rs; }
+  HIP_TRY(s, hipMemcpyAsync(s->fill_state_h, s->fill_state_d, sizeof(int32_t), hipMemcpyDeviceToHost, s->fill_stream));
   HIP_TRY(s, hipEventRecord(s->fill_done, s->fill_stream));
   return GSS_OK;
 }
@@ -520,6 +527,8 @@ void destroy_impl(gss_sampler* s) {
   for (int r = 0; r < GSS_MAX_RELATIONS; ++r) { dev_free(s, s->stamp[r]); dev_free(s, s->row_of[r]); dev_free(s, s->heavy_list[r]); }
   dev_free(s, s->state_d);
   if (s->state_h) (void)hipHostFree(s->state_h);
+  dev_free(s, s->fill_state_d);
+  if (s->fill_state_h) (void)hipHostFree(s->fill_state_h);
   if (s->user_ready) (void)hipEventDestroy(s->user_ready);
   release(s, s->checksum);
   delete s->timer;
@@ -535,38 +544,53 @@ const char* gss_version(void) { return "gss 0.2 (gfx950)"; }
 const char* gss_last_error(const gss_sampler* s) { return s ? s->err : g_create_err; }
 
 gss_status gss_create(const gss_graph* g, const gss_config* c, gss_sampler** out) {
-  if (!out) return GSS_ERR_INVALID_ARG;
+  return gss_create_tuned(g, c, nullptr, out);
+}
+
+gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_tuning* tune, gss_sampler** out) {
+  auto early = [](gss_status st, const char* what) { snprintf(g_create_err, sizeof g_create_err, "create: %s", what); return st; };
+  if (!out) return early(GSS_ERR_INVALID_ARG, "invalid argument (out is NULL)");
   *out = nullptr;
-  if (!g || !c || !g->num_nodes || !g->relations) return GSS_ERR_INVALID_ARG;
+  if (!g || !c || !g->num_nodes || !g->relations) return early(GSS_ERR_INVALID_ARG, "invalid argument");
   if (g->num_node_types < 1 || g->num_node_types > GSS_MAX_NODE_TYPES || g->num_relations < 1 ||
       g->num_relations > GSS_MAX_RELATIONS)
-    return GSS_ERR_INVALID_ARG;
-  if (c->k < 1 || c->k > GSS_MAX_K || c->num_layers < 1 || c->num_layers > GSS_MAX_LAYERS) return GSS_ERR_INVALID_ARG;
-  if ((int)c->mode < (int)GSS_MODE_FCR || (int)c->mode > (int)GSS_MODE_OTF_LAYER) return GSS_ERR_INVALID_ARG;
+    return early(GSS_ERR_INVALID_ARG, "invalid argument");
+  if (c->k < 1 || c->k > GSS_MAX_K || c->num_layers < 1 || c->num_layers > GSS_MAX_LAYERS) return early(GSS_ERR_INVALID_ARG, "invalid argument");
+  if ((int)c->mode < (int)GSS_MODE_FCR || (int)c->mode > (int)GSS_MODE_OTF_LAYER) return early(GSS_ERR_INVALID_ARG, "invalid argument");
   const bool m_fcr = c->mode == GSS_MODE_FCR || c->mode == GSS_MODE_SHARED_FCR || c->mode == GSS_MODE_OTF_LAYER;
   const bool m_otf = c->mode == GSS_MODE_OTF || c->mode == GSS_MODE_SHARED_OTF;
   const bool m_shared = c->mode == GSS_MODE_SHARED_OTF || c->mode == GSS_MODE_SHARED_FCR;
-  if (m_fcr && c->refresh_period < 1) return GSS_ERR_INVALID_ARG;
+  if (m_fcr && c->refresh_period < 1) return early(GSS_ERR_INVALID_ARG, "invalid argument");
   if ((m_otf || c->mode == GSS_MODE_OTF_FETCH || c->mode == GSS_MODE_OTF_LAYER) &&
       !(c->refresh_fraction >= 0.0 && c->refresh_fraction <= 1.0))
-    return GSS_ERR_INVALID_ARG;
-  if ((c->alloc == nullptr) != (c->free == nullptr)) return GSS_ERR_INVALID_ARG;
+    return early(GSS_ERR_INVALID_ARG, "invalid argument");
+  if ((c->alloc == nullptr) != (c->free == nullptr)) return early(GSS_ERR_INVALID_ARG, "invalid argument");
+  gss_tuning tn;
+  memset(&tn, 0, sizeof tn);
+  if (tune) tn = *tune;
+  if (tn.dedupe_layout < 0 || tn.dedupe_layout > 2 || tn.table_sets < 0 || tn.table_sets > MAX_TABLE_SETS ||
+      tn.pipeline_depth < 0 || tn.pipeline_depth > GSS_MAX_IN_FLIGHT || tn.steps_per_tick < 0 || tn.steps_per_tick > 2 ||
+      tn.insert_phase < 0 || tn.insert_phase > 2 || tn.scan_phase < 0 || tn.scan_phase > 1 || tn.tick_build < 0 ||
+      tn.tick_build > 2 || tn.first_dedupe_version >= VERSION_LAST)
+    return early(GSS_ERR_INVALID_ARG, "invalid argument (tuning field out of range)");
+  for (int32_t v : tn.reserved)
+    if (v != 0) return early(GSS_ERR_INVALID_ARG, "invalid argument (tuning: reserved fields must be 0)");
   int64_t total_nodes = 0;
   for (int t = 0; t < g->num_node_types; ++t) {
-    if (g->num_nodes[t] < 0 || g->num_nodes[t] >= (int64_t(1) << 31)) return GSS_ERR_INVALID_GRAPH;
+    if (g->num_nodes[t] < 0 || g->num_nodes[t] >= (int64_t(1) << 31)) return early(GSS_ERR_INVALID_GRAPH, "invalid graph");
     total_nodes += g->num_nodes[t];
   }
-  if (total_nodes >= (int64_t(1) << 32)) return GSS_ERR_INVALID_GRAPH;   // (type, id) must fit a 32-bit key
+  if (total_nodes >= (int64_t(1) << 32)) return early(GSS_ERR_INVALID_GRAPH, "invalid graph");   // (type, id) must fit a 32-bit key
   for (int r = 0; r < g->num_relations; ++r) {
     const gss_relation& q = g->relations[r];
     if (q.src_type < 0 || q.src_type >= g->num_node_types || q.dst_type < 0 || q.dst_type >= g->num_node_types ||
         !q.indptr || q.nnz < 0 || (q.nnz > 0 && !q.indices))
-      return GSS_ERR_INVALID_GRAPH;
-    if (!q.indptr_is_64 && q.nnz >= (int64_t(1) << 31)) return GSS_ERR_INVALID_GRAPH;
+      return early(GSS_ERR_INVALID_GRAPH, "invalid graph");
+    if (!q.indptr_is_64 && q.nnz >= (int64_t(1) << 31)) return early(GSS_ERR_INVALID_GRAPH, "invalid graph");
   }
 
   gss_sampler* s = new (std::nothrow) gss_sampler();
-  if (!s) return GSS_ERR_OOM;
+  if (!s) return early(GSS_ERR_OOM, "out of host memory");
   s->T = g->num_node_types; s->R = g->num_relations; s->L = c->num_layers; s->k = c->k; s->S = row_stride(c->k);
   s->mode = c->mode;
   s->fcr = m_fcr; s->otf = m_otf; s->shared = m_shared;
@@ -598,18 +622,16 @@ gss_status gss_create(const gss_graph* g, const gss_config* c, gss_sampler** out
     return bail(GSS_ERR_DEVICE);
   };
 
-  if (const char* ev = getenv("GSS_SCAN")) s->force_scan_kernel = !strcmp(ev, "kernel");
-  if (const char* ev = getenv("GSS_INSERT")) s->insert_policy = !strcmp(ev, "split") ? 1 : !strcmp(ev, "fused") ? 2 : 0;
-  if (const char* ev = getenv("GSS_TICK_BUILD")) s->dense_policy = !strcmp(ev, "dense") ? 1 : !strcmp(ev, "plain") ? 2 : 0;
+  s->force_scan_kernel = tn.scan_phase == 1;
+  s->insert_policy = tn.insert_phase;
+  s->dense_policy = tn.tick_build;
+  s->first_version = tn.first_dedupe_version ? tn.first_dedupe_version : VERSION_FIRST;
   s->tick_cap = tick_capacity(s->R, s->T);
   for (float& r : s->fill_ratio) r = 1.0f;
   // Dedupe table layout: one 8-byte word per node (no probing, one atomic per insert) unless that
-  // would be large; GSS_DEDUPE=hash|direct overrides the choice (used by the tests).
+  // would be large; gss_tuning.dedupe_layout overrides the choice.
   s->use_direct = (uint64_t)total_nodes * 8ull <= (8ull << 30);
-  if (const char* ev = getenv("GSS_DEDUPE")) {
-    if (!strcmp(ev, "hash")) s->use_direct = false;
-    if (!strcmp(ev, "direct")) s->use_direct = true;
-  }
+  if (tn.dedupe_layout) s->use_direct = tn.dedupe_layout == 1;
 
   s->state_words = ST_COUNTS + (GSS_MAX_LAYERS + 1) * s->T + GSS_MAX_LAYERS * s->R;
   const size_t state_bytes = sizeof(int32_t) * (size_t)s->state_words;
@@ -625,15 +647,12 @@ gss_status gss_create(const gss_graph* g, const gss_config* c, gss_sampler** out
   // -15 % per step; the epoch-refreshed modes gain nothing (their refresh kernel shares the chip with launches
   // twice as large) and keep one step per tick.
   s->steps_per_tick = (!s->otf && !s->fcr && s->R == 1 && s->T == 1) ? 2 : 1;
-  if (const char* ev = getenv("GSS_STEPS_PER_TICK")) s->steps_per_tick = (!s->otf && atoi(ev) == 2) ? 2 : 1;
+  if (tn.steps_per_tick) s->steps_per_tick = (!s->otf && tn.steps_per_tick == 2) ? 2 : 1;
   // A step of L hops has up to 4 L phases, one per launch: with two more steps than that in flight the step a
   // caller waits for has left the queue before.  (Deeper rings only widen the memory the launches touch: every slot
   // has scratch and a dedupe table of its own - 4 L + 4 was 1 % slower on the 1,024-seed workloads, 4 L too shallow.)
   s->ring = std::min(GSS_MAX_IN_FLIGHT, s->steps_per_tick * (4 * s->L + 2));
-  if (const char* ev = getenv("GSS_DEPTH")) {
-    const int v = atoi(ev);
-    if (v >= 1 && v <= GSS_MAX_IN_FLIGHT) s->ring = v;
-  }
+  if (tn.pipeline_depth) s->ring = tn.pipeline_depth;
   if ((e = hipStreamCreateWithFlags(&s->work, hipStreamNonBlocking)) != hipSuccess) { s->work = nullptr; return hipfail(e); }
   for (hipEvent_t& ev : s->tick_ev)
     if ((e = hipEventCreateWithFlags(&ev, hipEventDisableTiming)) != hipSuccess) { ev = nullptr; return hipfail(e); }
@@ -641,6 +660,11 @@ gss_status gss_create(const gss_graph* g, const gss_config* c, gss_sampler** out
     if ((e = hipStreamCreateWithFlags(&s->fill_stream, hipStreamNonBlocking)) != hipSuccess) { s->fill_stream = nullptr; return hipfail(e); }
     if ((e = hipEventCreateWithFlags(&s->fill_go, hipEventDisableTiming)) != hipSuccess) { s->fill_go = nullptr; return hipfail(e); }
     if ((e = hipEventCreateWithFlags(&s->fill_done, hipEventDisableTiming)) != hipSuccess) { s->fill_done = nullptr; return hipfail(e); }
+    s->fill_state_d = (int32_t*)dev_alloc(s, state_bytes);
+    if (!s->fill_state_d) return bail(GSS_ERR_OOM);
+    if ((e = hipMemsetAsync(s->fill_state_d, 0, state_bytes, s->stream)) != hipSuccess) return hipfail(e);
+    if ((e = hipHostMalloc((void**)&s->fill_state_h, state_bytes, hipHostMallocDefault)) != hipSuccess) { s->fill_state_h = nullptr; return hipfail(e); }
+    memset(s->fill_state_h, 0, state_bytes);
   }
 
   // The fill kernels index the adjacency through indptr: validate the graph before touching it.
@@ -680,7 +704,7 @@ gss_status gss_create(const gss_graph* g, const gss_config* c, gss_sampler** out
   // every `period` steps that is 2 + ring / period sets, three at least, MAX_TABLE_SETS at most) - when they are
   // small next to the free device memory (at most 1/8 of it all together), else two, else - when not even a
   // second one fits into half of it - one, refreshed in place after the steps in flight have drained.
-  // GSS_FCR_SETS=1..MAX_TABLE_SETS overrides (tests).
+  // gss_tuning.table_sets overrides.
   size_t set_bytes = 0;
   for (int r = 0; r < s->R; ++r) set_bytes += sizeof(int32_t) * (size_t)s->table_rows[r] * (size_t)s->S * (size_t)s->num_tables;
   if (s->fcr) {
@@ -689,10 +713,7 @@ gss_status gss_create(const gss_graph* g, const gss_config* c, gss_sampler** out
     const int want = std::min(MAX_TABLE_SETS, std::max(3, 2 + s->ring / std::max(1, s->period)));
     s->nsets = ((size_t)want * set_bytes <= free_b / 8) ? want : (3 * set_bytes <= free_b / 8) ? 3
                : (2 * set_bytes <= free_b / 2) ? 2 : 1;
-    if (const char* ev = getenv("GSS_FCR_SETS")) {
-      const int v = atoi(ev);
-      if (v >= 1 && v <= MAX_TABLE_SETS) s->nsets = v;
-    }
+    if (tn.table_sets) s->nsets = tn.table_sets;
   }
   for (int q = 0; q < s->nsets; ++q)
     for (int t = 0; t < s->num_tables; ++t)
@@ -786,7 +807,7 @@ static gss_status grow_slot(gss_sampler* s, Slot& sl, const Slot& plan, int L, i
     if (!need(sl.direct, sizeof(uint64_t) * (size_t)std::max<int64_t>(s->total_nodes, 1)))
       return fail(s, GSS_ERR_OOM, "step: dedupe table allocation failed");
     HIP_TRY(s, hipMemsetAsync(sl.direct.p, 0xFF, sl.direct.bytes, st));
-    sl.ver = VERSION_FIRST;
+    sl.ver = s->first_version;
   }
   if (!s->use_direct) {
     uint64_t cap = 1024;
@@ -794,7 +815,7 @@ static gss_status grow_slot(gss_sampler* s, Slot& sl, const Slot& plan, int L, i
     if (sl.hash.bytes < cap * sizeof(HashEntry)) {
       if (!need(sl.hash, cap * sizeof(HashEntry))) return fail(s, GSS_ERR_OOM, "step: dedupe table allocation failed");
       HIP_TRY(s, hipMemsetAsync(sl.hash.p, 0xFF, sl.hash.bytes, st));
-      sl.ver = VERSION_FIRST;
+      sl.ver = s->first_version;
     }
   }
   sl.hash_cap = s->use_direct ? 0 : sl.hash.bytes / sizeof(HashEntry);   // power of two by construction
@@ -949,7 +970,16 @@ gss_status gss_step_async(gss_sampler* s, const int32_t* seeds, int32_t num_seed
   // ---- Alg. 3: full refresh when the refresh epoch changes, into the set of tables that is not in use
   //      (stream order puts it after the steps that last read that set: their phases are all issued) ----
   if (s->fcr && epoch != s->epoch) {
-    if (s->prefetched_epoch >= 0) HIP_TRY(s, hipStreamWaitEvent(st, s->fill_done, 0));   // the idle set is being written
+    if (s->prefetched_epoch >= 0) {      // the idle set is being (or has been) written on the fill stream
+      HIP_TRY(s, hipStreamWaitEvent(st, s->fill_done, 0));
+      // the refresh started an epoch ago and is normally long done: its error flag is checked here, before any
+      // step reads its rows
+      HIP_TRY(s, hipEventSynchronize(s->fill_done));
+      if (s->fill_state_h[ST_ERROR] != 0) {
+        s->poisoned = true;
+        return fail(s, GSS_ERR_DEVICE, "refresh: device error flag 0x%x", s->fill_state_h[ST_ERROR]);
+      }
+    }
     if (!prefetched) {                   // (a step number jumped over the epoch computed ahead, or none was)
       gss_status rs = fill_all_tables(s, (uint32_t)(epoch * s->period), sl.state_d, st, fill_set, s->cur_set);
       if (rs != GSS_OK) { s->poisoned = true; return rs; }

@@ -22,7 +22,7 @@ GSS_MODE_FCR, GSS_MODE_OTF, GSS_MODE_SHARED_OTF, GSS_MODE_FBL, GSS_MODE_SHARED_F
 GSS_MAX_K = 32
 GSS_MAX_IN_FLIGHT = 32
 
-EXPORTS = ["gss_create", "gss_step", "gss_destroy", "gss_cache_read", "gss_cache_checksum",
+EXPORTS = ["gss_create", "gss_create_tuned", "gss_step", "gss_destroy", "gss_cache_read", "gss_cache_checksum",
            "gss_last_error", "gss_version", "gss_profile_enable", "gss_profile_read", "gss_step_async", "gss_step_wait",
            "gss_cache_bytes", "gss_gather_rows", "gss_pipeline_depth"]
 KERNEL_NAMES = ["fill_full", "step_tick"]
@@ -48,6 +48,12 @@ class gss_config(C.Structure):
                 ("rng_seed", C.c_uint64), ("hip_stream", C.c_void_p),
                 ("alloc", ALLOC_FN), ("free", FREE_FN), ("alloc_ctx", C.c_void_p),
                 ("degree_threshold", C.c_int32)]
+
+
+class gss_tuning(C.Structure):
+    _fields_ = [("dedupe_layout", C.c_int32), ("table_sets", C.c_int32), ("pipeline_depth", C.c_int32),
+                ("steps_per_tick", C.c_int32), ("insert_phase", C.c_int32), ("scan_phase", C.c_int32),
+                ("tick_build", C.c_int32), ("first_dedupe_version", C.c_uint32), ("reserved", C.c_int32 * 8)]
 
 
 class gss_block_nodes(C.Structure):
@@ -81,6 +87,8 @@ def load_library():
     L = C.CDLL(LIB_PATH)
     L.gss_create.argtypes = [C.POINTER(gss_graph), C.POINTER(gss_config), C.POINTER(C.c_void_p)]
     L.gss_create.restype = C.c_int
+    L.gss_create_tuned.argtypes = [C.POINTER(gss_graph), C.POINTER(gss_config), C.POINTER(gss_tuning), C.POINTER(C.c_void_p)]
+    L.gss_create_tuned.restype = C.c_int
     L.gss_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32,
                            C.c_int64, C.POINTER(gss_blocks)]
     L.gss_step.restype = C.c_int
@@ -199,7 +207,9 @@ class Sampler:
 
     def __init__(self, num_nodes: Sequence[int], relations: Sequence[DeviceRelation], k: int, mode: int,
                  num_layers: int, refresh_fraction: float = 0.0, refresh_period: int = 1, rng_seed: int = 0,
-                 device="cuda:0", degree_threshold: int = -1):
+                 device="cuda:0", degree_threshold: int = -1, tuning: Dict[str, int] = None, allocator=None):
+        """`tuning`: fields of gss_tuning by name (layout choices; results do not depend on them).  `allocator`: an
+        object with alloc_cb / free_cb / view_i32 like _TorchAllocator (default: a new _TorchAllocator)."""
         import torch
         self.torch = torch
         self._lib = load_library()
@@ -209,7 +219,7 @@ class Sampler:
         self.relations = list(relations)
         self.k, self.mode, self.num_layers = k, mode, num_layers
         self.num_tables = 0 if mode == GSS_MODE_FBL else (1 if mode in (GSS_MODE_SHARED_OTF, GSS_MODE_SHARED_FCR) else num_layers)
-        self._allocator = _TorchAllocator(self.device)
+        self._allocator = allocator if allocator is not None else _TorchAllocator(self.device)
         nn = (C.c_int64 * len(self.num_nodes))(*self.num_nodes)
         rels = (gss_relation * len(self.relations))()
         for i, r in enumerate(self.relations):
@@ -225,7 +235,8 @@ class Sampler:
                          self._stream.cuda_stream, self._allocator.alloc_cb, self._allocator.free_cb, None,
                          degree_threshold)
         h = C.c_void_p()
-        st = self._lib.gss_create(C.byref(g), C.byref(cfg), C.byref(h))
+        tn = gss_tuning(**(tuning or {}))
+        st = self._lib.gss_create_tuned(C.byref(g), C.byref(cfg), C.byref(tn), C.byref(h))
         if st != GSS_OK:
             raise GssError(st, "gss_create failed: " + self._lib.gss_last_error(None).decode())
         self._h = h

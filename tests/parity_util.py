@@ -6,6 +6,16 @@ from oracle import gsso
 from paper_2406_17918_amd import synth
 
 
+# Layout choices (fields of gss_tuning) applied to every GPU sampler the helpers create: results never depend on them,
+# which is what the tests that set them check.  Set through the `tuning` fixture of conftest.py.
+_tuning = {}
+
+
+def set_tuning(**fields):
+    _tuning.clear()
+    _tuning.update(fields)
+
+
 def oracle_sampler(graph, w_or_kw):
     kw = w_or_kw if isinstance(w_or_kw, dict) else dict(
         k=w_or_kw.k, mode=w_or_kw.mode, num_layers=len(w_or_kw.fanouts), refresh_fraction=w_or_kw.refresh_fraction,
@@ -21,7 +31,7 @@ def gpu_sampler(graph, w_or_kw, dev_rels=None):
         refresh_period=w_or_kw.refresh_period, rng_seed=w_or_kw.rng_seed)
     if dev_rels is None:
         dev_rels = gss.upload_graph(graph)
-    return gss.Sampler(graph.num_nodes, dev_rels, **kw)
+    return gss.Sampler(graph.num_nodes, dev_rels, tuning=dict(_tuning), **kw)
 
 
 def assert_blocks_equal(gpu_blocks, ora_blocks, ctx=""):

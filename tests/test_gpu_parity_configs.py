@@ -19,7 +19,7 @@ def graph_for(name):
     return _graphs[key]
 
 
-@pytest.mark.parametrize("name,full_every", [("cfg1_tiny_otf", 1), ("cfg2_medium_fcr", 10), ("cfg3_large_otf", 0),
+@pytest.mark.parametrize("name,full_every", [("cfg1_tiny_otf", 1), ("cfg2_medium_fcr", 1), ("cfg3_large_otf", 0),
                                              ("cfg4_large_shared", 0), ("cfg5_hetero_otf", 0)])
 def test_workload_parity(name, full_every):
     w = synth.WORKLOADS[name]

@@ -138,9 +138,9 @@ def test_device_detected_errors():
 
 
 @pytest.mark.parametrize("layout", ["hash", "direct"])
-def test_parity_both_dedupe_table_layouts(layout, monkeypatch):
-    # the library picks the direct (one word per node) layout by itself; GSS_DEDUPE forces either one
-    monkeypatch.setenv("GSS_DEDUPE", layout)
+def test_parity_both_dedupe_table_layouts(layout, tuning):
+    # the library picks the direct (one word per node) layout by itself; gss_tuning.dedupe_layout forces either one
+    tuning(dedupe_layout={"direct": 1, "hash": 2}[layout])
     g = graph_small()
     for k, mode, frac, fanouts, batch in [(20, OTF, 0.2, [15, 10, 5], 257), (30, SHARED, 0.1, [15, 10, 5], 300), (20, FCR, 0.0, [7, 7], 64)]:
         kw = dict(k=k, mode=mode, num_layers=len(fanouts), refresh_fraction=frac, refresh_period=2, rng_seed=99)
@@ -187,9 +187,9 @@ def test_async_pipeline_matches_blocking_steps():
     gs.close()
 
 
-def test_parity_with_separate_scan_launch(monkeypatch):
+def test_parity_with_separate_scan_launch(tuning):
     # hops with more than 4096 tiles hand the tile scan to a one-workgroup kernel; force that path on a small graph
-    monkeypatch.setenv("GSS_SCAN", "kernel")
+    tuning(scan_phase=1)
     g = graph_small()
     kw = dict(k=20, mode=OTF, num_layers=3, refresh_fraction=0.2, refresh_period=1, rng_seed=5)
     assert run_parity(g, kw, [15, 10, 5], 257, steps=range(4)) > 0
@@ -200,10 +200,10 @@ def test_parity_with_separate_scan_launch(monkeypatch):
 
 @pytest.mark.parametrize("insert", ["", "split"])
 @pytest.mark.parametrize("k,mode,frac,period,fanouts,batch", [c for c in CASES if c[0] in (10, 20, 30, 12, 8, 9, 5, 32)])
-def test_pipelined_steps_small_graph(k, mode, frac, period, fanouts, batch, insert, monkeypatch):
+def test_pipelined_steps_small_graph(k, mode, frac, period, fanouts, batch, insert, tuning):
     # a full pipeline of steps in flight: every launch carries one phase of each of them ("split": every hop's dedupe
     # table inserts run as a phase of their own, which by default only large hops do)
-    monkeypatch.setenv("GSS_INSERT", insert)
+    tuning(insert_phase=1 if insert == "split" else 0)
     g = graph_small()
     kw = dict(k=k, mode=mode, num_layers=len(fanouts), refresh_fraction=frac, refresh_period=period, rng_seed=31337)
     assert run_parity_pipelined(g, kw, fanouts, batch, steps=range(40)) > 0
@@ -211,12 +211,12 @@ def test_pipelined_steps_small_graph(k, mode, frac, period, fanouts, batch, inse
 
 @pytest.mark.parametrize("scan,insert", [("emit", "fused"), ("kernel", "split"), ("emit", "split")])
 @pytest.mark.parametrize("mode,frac", [(OTF, 0.25), (FCR, 0.0), (FBL, 0.0), (SHARED, 0.2), (SHARED_FCR, 0.0), (OTF_FETCH, 0.5)])
-def test_pipelined_steps_with_varying_layer_counts_and_irregular_waits(mode, frac, scan, insert, monkeypatch):
+def test_pipelined_steps_with_varying_layer_counts_and_irregular_waits(mode, frac, scan, insert, tuning):
     # steps in flight use 1, 2 or 3 of the 3 layers, skip step numbers (FCR epochs change at irregular points), and
     # the caller collects at irregular points: every step's blocks equal the oracle's, and so do the tables
     import torch
-    monkeypatch.setenv("GSS_SCAN", scan)                   # "kernel": hops get a separate scan phase
-    monkeypatch.setenv("GSS_INSERT", insert)               # "split": and a separate insert phase (up to 5 phases per hop)
+    # "kernel": hops get a separate scan phase; "split": and a separate insert phase (up to 5 phases per hop)
+    tuning(scan_phase=1 if scan == "kernel" else 0, insert_phase={"split": 1, "fused": 2}[insert])
     g = graph_small()
     kw = dict(k=12, mode=mode, num_layers=3, refresh_fraction=frac, refresh_period=3, rng_seed=8)
     gs, os_ = gpu_sampler(g, kw), oracle_sampler(g, kw)
@@ -337,13 +337,12 @@ def test_parity_degree_split_typed_graph_and_hubs():
 @pytest.mark.parametrize("per_tick", ["1", "2"])
 @pytest.mark.parametrize("sets", ["1", "2", "3", "5"])
 @pytest.mark.parametrize("mode,period", [(FCR, 1), (FCR, 2), (FCR, 5), (SHARED_FCR, 3), (FCR, 11), (OTF_LAYER, 1), (OTF_LAYER, 4)])
-def test_fcr_refresh_with_steps_in_flight(mode, period, sets, per_tick, monkeypatch):
+def test_fcr_refresh_with_steps_in_flight(mode, period, sets, per_tick, tuning):
     # FCR keeps 1-3 sets of tables: the next epoch's rows are computed ahead of time into a set no step in flight
     # reads (one set: in place, after the steps in flight have issued all their phases).  Step numbers jump over
     # epochs now and then, so the rows computed ahead are sometimes for the wrong epoch.
     import torch
-    monkeypatch.setenv("GSS_FCR_SETS", sets)
-    monkeypatch.setenv("GSS_STEPS_PER_TICK", per_tick)     # "2": a launch starts two steps (up to 24 slices, the compact form)
+    tuning(table_sets=int(sets), steps_per_tick=int(per_tick))   # 2 per tick: a launch starts two steps (up to 24 slices, the compact form)
     g = graph_small()
     kw = dict(k=12, mode=mode, num_layers=3, refresh_fraction=0.25 if mode == OTF_LAYER else 0.0, refresh_period=period, rng_seed=17)
     steps = [t for t in range(60) if t not in (7, 8, 9, 10, 11, 12, 13, 29, 41, 42)]
@@ -450,10 +449,10 @@ def test_blocks_of_a_collected_step_stay_valid_while_later_steps_grow_the_buffer
 
 @pytest.mark.parametrize("build", ["dense", "plain"])
 @pytest.mark.parametrize("k,mode,frac,period,fanouts,batch", [c for c in CASES if c[0] in (20, 30, 32, 9, 8)])
-def test_both_register_budgets_of_the_step_kernel(k, mode, frac, period, fanouts, batch, build, monkeypatch):
+def test_both_register_budgets_of_the_step_kernel(k, mode, frac, period, fanouts, batch, build, tuning):
     # the step kernel is built twice (seven or eight workgroups per CU); launches choose by their size, which these
     # small cases never reach: force either build for every launch
-    monkeypatch.setenv("GSS_TICK_BUILD", build)
+    tuning(tick_build={"dense": 1, "plain": 2}[build])
     g = graph_small()
     kw = dict(k=k, mode=mode, num_layers=len(fanouts), refresh_fraction=frac, refresh_period=period, rng_seed=99)
     assert run_parity(g, kw, fanouts, batch, steps=[0, 1, 2, 5]) > 0
@@ -461,8 +460,8 @@ def test_both_register_budgets_of_the_step_kernel(k, mode, frac, period, fanouts
 
 
 @pytest.mark.parametrize("build", ["dense", "plain"])
-def test_both_register_budgets_typed_graph(build, monkeypatch):
-    monkeypatch.setenv("GSS_TICK_BUILD", build)
+def test_both_register_budgets_typed_graph(build, tuning):
+    tuning(tick_build={"dense": 1, "plain": 2}[build])
     gt = synth.hetero_graph([1200, 2000, 60, 300], [(1, 2, 2600), (1, 0, 9000), (0, 0, 5000), (0, 3, 8000)], 2.2, seed=8)
     kw = dict(k=25, mode=OTF, num_layers=2, refresh_fraction=0.2, refresh_period=1, rng_seed=3)
     assert run_parity_pipelined(gt, kw, [25, 20], 100, steps=range(12)) > 0

@@ -1,0 +1,117 @@
+"""GPU tests of the host driver's failure handling and rarely taken paths: an allocator that runs out of memory
+(at gss_create and while a step's buffers grow), the wrap-around of the dedupe-table version counter, and the
+hashed dedupe layout at the size of the large workload.  Every kernel exits normally in all of them."""
+import numpy as np
+import pytest
+
+from oracle import gsso
+from paper_2406_17918_amd import synth
+from parity_util import run_parity, run_parity_pipelined, oracle_sampler, assert_blocks_equal
+
+pytestmark = pytest.mark.gpu
+
+
+def failing_allocator(fail_at=None):
+    from paper_2406_17918_amd import gss
+
+    class Failing(gss._TorchAllocator):
+        """PyTorch's caching allocator, except that call number `fail_at` (1-based) returns NULL."""
+
+        def __init__(self):
+            super().__init__("cuda:0")
+            self.calls = 0
+            self.fail_at = fail_at
+
+        def _alloc(self, ctx, nbytes):
+            self.calls += 1
+            if self.fail_at is not None and self.calls == self.fail_at:
+                return None
+            return super()._alloc(ctx, nbytes)
+
+    return Failing()
+
+
+@pytest.mark.parametrize("mode,frac,theta", [(gsso.MODE_FCR, 0.0, -1), (gsso.MODE_SHARED_OTF, 0.25, 3), (gsso.MODE_OTF, 0.25, -1)])
+def test_allocator_returning_null_at_create(mode, frac, theta):
+    # every allocation of gss_create fails once: GSS_ERR_OOM, no handle, and everything handed out before is returned
+    from paper_2406_17918_amd import gss
+    g = synth.chunglu_graph(2000, 15000, 2.2, 5)
+    rels = gss.upload_graph(g)
+    kw = dict(k=8, mode=mode, num_layers=2, refresh_fraction=frac, refresh_period=2, rng_seed=1, degree_threshold=theta)
+    probe = failing_allocator()
+    gss.Sampler(g.num_nodes, rels, allocator=probe, **kw).close()
+    assert probe.calls >= 5 and not probe.live
+    for n in range(1, probe.calls + 1):
+        a = failing_allocator(n)
+        with pytest.raises(gss.GssError) as e:
+            gss.Sampler(g.num_nodes, rels, allocator=a, **kw)
+        assert e.value.status == gss.GSS_ERR_OOM, n
+        assert not a.live, (n, len(a.live))
+
+
+@pytest.mark.parametrize("layout", [1, 2])
+def test_allocator_returning_null_while_a_step_grows_its_buffers(layout):
+    # the n-th allocation of the first step (and of a later, larger one) fails: GSS_ERR_OOM, the sampler is unchanged -
+    # the same step then succeeds and equals the oracle's - and destroy returns everything
+    import torch
+    from paper_2406_17918_amd import gss
+    g = synth.chunglu_graph(2000, 15000, 2.2, 5)
+    rels = gss.upload_graph(g)
+    kw = dict(k=8, mode=gsso.MODE_OTF, num_layers=2, refresh_fraction=0.25, refresh_period=1, rng_seed=1)
+    fan = [4, 5]
+    probe = failing_allocator()
+    s = gss.Sampler(g.num_nodes, rels, allocator=probe, tuning=dict(dedupe_layout=layout, pipeline_depth=3), **kw)
+    created = probe.calls
+    s.step(torch.from_numpy(synth.seeds_for_step(2000, 50, 1, 0)).cuda(), fan, 0)
+    first_step = probe.calls - created
+    s.close()
+    assert first_step >= 8 and not probe.live
+    for n in list(range(1, first_step + 1, 3)) + [first_step]:
+        a = failing_allocator()
+        s = gss.Sampler(g.num_nodes, rels, allocator=a, tuning=dict(dedupe_layout=layout, pipeline_depth=3), **kw)
+        o = oracle_sampler(g, kw)
+        seeds = synth.seeds_for_step(2000, 50, 1, 0)
+        a.fail_at = a.calls + n
+        with pytest.raises(gss.GssError) as e:
+            s.step(torch.from_numpy(seeds).cuda(), fan, 0)
+        assert e.value.status == gss.GSS_ERR_OOM, n
+        a.fail_at = None
+        assert_blocks_equal(s.step(torch.from_numpy(seeds).cuda(), fan, 0), o.step(seeds, fan, 0), ctx=f"retry after failure {n}")
+        # a larger batch grows the buffers again; fail the first of those allocations
+        big = synth.seeds_for_step(2000, 400, 1, 1)
+        a.fail_at = a.calls + 1
+        with pytest.raises(gss.GssError) as e:
+            s.step(torch.from_numpy(big).cuda(), fan, 1)
+        assert e.value.status == gss.GSS_ERR_OOM
+        a.fail_at = None
+        assert_blocks_equal(s.step(torch.from_numpy(big).cuda(), fan, 1), o.step(big, fan, 1), ctx="larger batch")
+        for t in range(2):
+            assert np.array_equal(s.cache(t).cpu().numpy(), o.cache(t))
+        s.close()
+        o.close()
+        assert not a.live, (n, len(a.live))
+
+
+@pytest.mark.parametrize("layout", [1, 2])
+def test_dedupe_version_counter_wraps(layout, tuning):
+    # every hop of every step takes a fresh version of its slot's dedupe table, so that the table is never cleared
+    # between hops; started a few versions before the end of the version space, the counter wraps within a few
+    # steps: the table is cleared once and the versions start over
+    tuning(dedupe_layout=layout, pipeline_depth=2, first_dedupe_version=0xFFFFFFF0 - 7)
+    g = synth.chunglu_graph(3000, 30000, 2.2, 21)
+    for mode, frac in [(gsso.MODE_OTF, 0.2), (gsso.MODE_FCR, 0.0)]:
+        kw = dict(k=20, mode=mode, num_layers=3, refresh_fraction=frac, refresh_period=2, rng_seed=99)
+        assert run_parity(g, kw, [15, 10, 5], 200, steps=range(12)) > 0
+        assert run_parity_pipelined(g, kw, [15, 10, 5], 200, steps=range(14)) > 0
+
+
+def test_hashed_dedupe_layout_on_the_large_graph(tuning):
+    # the open-addressing layout (the library's choice above 8 GiB of direct words) at the size of the large
+    # workload: 2.45 M nodes, frontiers of 20k nodes, 313k picks per step
+    tuning(dedupe_layout=2)
+    w = synth.WORKLOADS["cfg3_large_otf"]
+    g = w.make_graph()
+    steps = list(range(8))
+    total = run_parity(g, w, w.fanouts, w.batch, steps, workload_seed=w.workload_seed, full_cache_every=10**9)
+    total2 = run_parity_pipelined(g, w, w.fanouts, w.batch, steps, workload_seed=w.workload_seed)
+    assert total2 == total > 0
