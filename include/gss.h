@@ -220,6 +220,18 @@ gss_status gss_cache_read(gss_sampler* s, int32_t layer, int32_t relation, int32
  * index) of mix(c * 0x9E3779B97F4A7C15 + (uint32)value), mix = the splitmix64 finaliser.  *out: host. */
 gss_status gss_cache_checksum(gss_sampler* s, int32_t layer, int32_t relation, uint64_t* out);
 
+/* gss_cache_checksum for callers that cannot allocate device memory or wait for the device: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  The same checksum of table (layer, relation), written
+ * to *out_device (device memory, 8 bytes, 8-byte aligned) by two kernels enqueued on hip_stream (hipStream_t; NULL = the
+ * default stream); the call does not wait for them, allocates nothing and calls no allocating routine.  The per-chunk
+ * partial sums live in a static device array of the library (128 KB on every GPU it runs on, held until the process
+ * ends), which bounds the table: num_nodes[dst_type] * k <= GSS_CHECKSUM_STATIC_MAX_CELLS, else GSS_ERR_INVALID_ARG.
+ * All calls on one GPU share that array: calls that overlap on one GPU (different streams or threads) race.
+ * No step may be in flight on the handle (GSS_ERR_INVALID_ARG otherwise), and hip_stream must be ordered after the
+ * handle's earlier work by the caller (gss_step / gss_step_wait return only after a step's kernels are done). */
+#define GSS_CHECKSUM_STATIC_MAX_CELLS (1ll << 28)
+gss_status gss_cache_checksum_static(gss_sampler* s, int32_t layer, int32_t relation, uint64_t* out_device, void* hip_stream);
+
 /* Device memory held by the cache itself, in bytes: tables (the epoch-refreshed modes keep up to five sets of
  * them, so that a refresh never waits for steps in flight: as many as the epochs the steps in flight can span plus
  * one, three at least, when that takes at most 1/8 of the free device memory at gss_create, else two, else one),

@@ -1131,4 +1131,18 @@ gss_status gss_cache_checksum(gss_sampler* s, int32_t layer, int32_t relation, u
   return GSS_OK;
 }
 
+gss_status gss_cache_checksum_static(gss_sampler* s, int32_t layer, int32_t relation, uint64_t* out_device, void* hip_stream) {
+  if (!s || !out_device || layer < 0 || layer >= s->num_tables || relation < 0 || relation >= s->R)
+    return fail(s, GSS_ERR_INVALID_ARG, "cache_checksum_static: invalid argument");
+  if (((uintptr_t)out_device & 7u) != 0) return fail(s, GSS_ERR_INVALID_ARG, "cache_checksum_static: out_device is not 8-byte aligned");
+  if (oldest_pending(s)) return fail(s, GSS_ERR_INVALID_ARG, "cache_checksum_static: collect the steps in flight first");
+  const int64_t n = s->num_nodes[s->rel[relation].dst_type];
+  if (n * (int64_t)s->k > (int64_t)GSS_CHECKSUM_STATIC_MAX_CELLS)
+    return fail(s, GSS_ERR_INVALID_ARG, "cache_checksum_static: %lld cells exceed the static scratch (at most %lld)",
+                (long long)(n * s->k), (long long)GSS_CHECKSUM_STATIC_MAX_CELLS);
+  HIP_TRY(s, launch_cache_checksum_static(s->table[s->cur_set][layer][relation], s->row_of[relation], n, s->k, s->S,
+                                          (unsigned long long*)out_device, (hipStream_t)hip_stream));
+  return GSS_OK;
+}
+
 }  // extern "C"

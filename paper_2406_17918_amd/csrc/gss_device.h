@@ -211,6 +211,10 @@ hipError_t launch_cache_read(const int32_t* table, const int32_t* row_of, int64_
                              hipStream_t st);
 hipError_t launch_cache_checksum(const int32_t* table, const int32_t* row_of, int64_t n, int k, int S,
                                  unsigned long long* out, hipStream_t st);
+// The checksum into a device word, with partial sums in the library's static scratch array: allocates nothing.
+// n * k must not exceed GSS_CHECKSUM_STATIC_MAX_CELLS.
+hipError_t launch_cache_checksum_static(const int32_t* table, const int32_t* row_of, int64_t n, int k, int S,
+                                        unsigned long long* out, hipStream_t st);
 // Degree split: row_of[v] = rank of v among the nodes with deg > theta, or -1; *num_rows = their number.
 // `chunk_counts` is scratch of ceil(n / 1024) + 1 words.
 hipError_t launch_build_row_map(const void* indptr, int is64, int64_t n, int32_t theta, int32_t* chunk_counts,

@@ -1073,6 +1073,51 @@ __global__ void cache_checksum_kernel(const int32_t* table, const int32_t* row_o
   if (lane_id() == 0) atomicAdd(out, (unsigned long long)sum);
 }
 
+// The same checksum without any allocation: every workgroup reduces one chunk of CK_CHUNK cells into its own word of a
+// static scratch array (no atomics, nothing to clear), and a second one-workgroup kernel adds the words up into the
+// caller's device word.  The array's name is only a host-side stand-in: kernels get the address that
+// hipGetSymbolAddress returns for the current device (each GPU holds its own copy).
+constexpr int CK_CHUNK = 16384;
+constexpr int CK_MAX_PARTIALS = (int)(GSS_CHECKSUM_STATIC_MAX_CELLS / CK_CHUNK);
+static __device__ __align__(256) unsigned long long scratch[CK_MAX_PARTIALS];   // 128 KB on every GPU the library runs on
+
+__device__ __forceinline__ uint64_t block_sum_u64(uint64_t sum, unsigned long long* lds) {   // 256 threads; valid in thread 0
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const uint32_t lo = __shfl_down((uint32_t)sum, o), hi = __shfl_down((uint32_t)(sum >> 32), o);
+    sum += ((uint64_t)hi << 32) | lo;
+  }
+  if (lane_id() == 0) lds[threadIdx.x >> 6] = sum;
+  __syncthreads();
+  return lds[0] + lds[1] + lds[2] + lds[3];
+}
+
+__global__ __launch_bounds__(256) void checksum_partials_kernel(const int32_t* table, const int32_t* row_of, int64_t n, int k,
+                                                                int S, unsigned long long* partials) {
+  __shared__ unsigned long long lds[4];
+  const int64_t total = n * k, c0 = (int64_t)blockIdx.x * CK_CHUNK;
+  uint64_t sum = 0;
+  for (int i = (int)threadIdx.x; i < CK_CHUNK; i += 256) {
+    const int64_t c = c0 + i;
+    if (c >= total) break;
+    const int64_t v = c / k;
+    const int j = (int)(c - v * k);
+    const int64_t at = row_of ? (int64_t)row_of[v] : v;
+    const int val = at >= 0 ? table[at * S + j] : -1;
+    sum += mix64((uint64_t)c * 0x9E3779B97F4A7C15ull + (uint64_t)(uint32_t)val);
+  }
+  const uint64_t t = block_sum_u64(sum, lds);
+  if (threadIdx.x == 0) partials[blockIdx.x] = t;
+}
+
+__global__ __launch_bounds__(256) void checksum_finish_kernel(const unsigned long long* partials, int count, unsigned long long* out) {
+  __shared__ unsigned long long lds[4];
+  uint64_t sum = 0;
+  for (int i = (int)threadIdx.x; i < count; i += 256) sum += partials[i];
+  const uint64_t t = block_sum_u64(sum, lds);
+  if (threadIdx.x == 0) *out = t;
+}
+
 // Row map of the degree split (built once, when the sampler is created).  Nodes are taken in chunks
 // of 1024: count the nodes with deg > theta per chunk, scan the chunk counts (one workgroup), then
 // number the nodes of every chunk.
@@ -1322,6 +1367,31 @@ hipError_t launch_cache_checksum(const int32_t* table, const int32_t* row_of, in
                                  unsigned long long* out, hipStream_t st) {
   const unsigned grid = clamp_grid((n * k + 255) / 256, 4096);
   hipLaunchKernelGGL(cache_checksum_kernel, dim3(grid), dim3(256), 0, st, table, row_of, n, k, S, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_cache_checksum_static(const int32_t* table, const int32_t* row_of, int64_t n, int k, int S,
+                                        unsigned long long* out, hipStream_t st) {
+  constexpr int MAX_DEVICES = 64;
+  static unsigned long long* scratch_of[MAX_DEVICES];     // device address of `scratch`, per device (set once; racing
+  int dev = -1;                                            // first calls store the same value)
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  if (!scratch_of[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    scratch_of[dev] = (unsigned long long*)p;
+  }
+  const int64_t total = n * k;
+  if (total > (int64_t)GSS_CHECKSUM_STATIC_MAX_CELLS) return hipErrorInvalidValue;
+  const int chunks = (int)((total + CK_CHUNK - 1) / CK_CHUNK);
+  unsigned long long* partials = scratch_of[dev];
+  if (chunks > 0)
+    hipLaunchKernelGGL(checksum_partials_kernel, dim3((unsigned)chunks), dim3(256), 0, st, table, row_of, n, k, S, partials);
+  hipLaunchKernelGGL(checksum_finish_kernel, dim3(1), dim3(256), 0, st, (const unsigned long long*)partials, chunks, out);
   return hipGetLastError();
 }
 

@@ -24,7 +24,7 @@ GSS_MAX_IN_FLIGHT = 32
 
 EXPORTS = ["gss_create", "gss_create_tuned", "gss_step", "gss_destroy", "gss_cache_read", "gss_cache_checksum",
            "gss_last_error", "gss_version", "gss_profile_enable", "gss_profile_read", "gss_step_async", "gss_step_wait",
-           "gss_cache_bytes", "gss_gather_rows", "gss_pipeline_depth"]
+           "gss_cache_bytes", "gss_gather_rows", "gss_pipeline_depth", "gss_cache_checksum_static"]
 KERNEL_NAMES = ["fill_full", "step_tick"]
 
 
@@ -102,6 +102,8 @@ def load_library():
     L.gss_cache_read.restype = C.c_int
     L.gss_cache_checksum.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.POINTER(C.c_uint64)]
     L.gss_cache_checksum.restype = C.c_int
+    L.gss_cache_checksum_static.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    L.gss_cache_checksum_static.restype = C.c_int
     L.gss_cache_bytes.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
     L.gss_cache_bytes.restype = C.c_int
     L.gss_pipeline_depth.argtypes = [C.c_void_p]
@@ -337,6 +339,15 @@ class Sampler:
         if st != GSS_OK:
             raise GssError(st, "gss_cache_bytes failed")
         return v.value
+
+    def checksum_static(self, out, layer: int = 0, relation: int = 0) -> None:
+        """gss_cache_checksum_static: the checksum into `out` (a device int64 tensor of one element), enqueued on
+        torch's current stream and not waited for."""
+        assert out.is_cuda and out.numel() == 1 and out.element_size() == 8
+        st = self._lib.gss_cache_checksum_static(self._h, layer, relation, out.data_ptr(),
+                                                 self.torch.cuda.current_stream(self.device).cuda_stream)
+        if st != GSS_OK:
+            raise GssError(st, self._lib.gss_last_error(self._h).decode())
 
     def checksum(self, layer: int = 0, relation: int = 0) -> int:
         v = C.c_uint64()
