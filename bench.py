@@ -87,11 +87,14 @@ def fill_full_bytes(w, graph):
     return total
 
 
+TUNING = {}       # --tuning field=value ...: layout choices (gss_tuning) for every sampler of the run; results do not depend on them
+
+
 def make_sampler(w, dev_rels, graph):
     from paper_2406_17918_amd import gss
     return gss.Sampler(graph.num_nodes, dev_rels, k=w.k, mode=w.mode, num_layers=len(w.fanouts),
                        refresh_fraction=w.refresh_fraction, refresh_period=w.refresh_period, rng_seed=w.rng_seed,
-                       degree_threshold=getattr(w, "degree_threshold", -1))
+                       degree_threshold=getattr(w, "degree_threshold", -1), tuning=dict(TUNING))
 
 
 def run_gpu(w, graph, steps, warmup, profile_steps, steady_steps=0, blocking_steps=0):
@@ -468,7 +471,12 @@ def main():
     ap.add_argument("--gather", action="store_true",
                     help="instead of the sampler benchmark, time the feature gather H[src_nodes] on --workload's minibatches")
     ap.add_argument("--feature-dim", type=int, default=128)
+    ap.add_argument("--tuning", nargs="*", default=[], metavar="FIELD=VALUE",
+                    help="fields of gss_tuning (launch layout choices; A/B measurements), e.g. visit_once=2 pipeline_depth=8")
     a = ap.parse_args()
+    for kv in a.tuning:
+        key, val = kv.split("=")
+        TUNING[key] = int(val)
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU (one replica of the sampler per GPU needs no communication); "
               "--gpus must be 1", file=sys.stderr)
@@ -518,6 +526,8 @@ def main():
         "ms_per_step": head.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int32", "data": "synthetic", "library": lib_version,
     }
+    if TUNING:
+        out["tuning"] = dict(TUNING)
     out.update(head)
     if not a.only and a.batch == 0:
         key_of = lambda n: "large" if n in ("cfg3_large_otf", "cfg4_large_shared") else n

@@ -170,7 +170,15 @@ typedef struct {
   int32_t scan_phase;           /* 1: every hop gets a separate scan phase                                           */
   int32_t tick_build;           /* 1: every launch uses the step kernel's 8-workgroups-per-CU build, 2: none does     */
   uint32_t first_dedupe_version;/* start of each slot's dedupe-table version counter (tests of the wrap-around)       */
-  int32_t reserved[8];          /* must be 0                                                                          */
+  int32_t visit_once;           /* SHARED_OTF on a graph with one relation.  Default: the steps of gss_step_async run as
+                                   visit-once steps where their size allows (each node is visited by the first hop that
+                                   reaches it and draws the picks of all its remaining hops there: one dependent launch
+                                   per hop, the rest of the work trails behind in the launches of later steps), those of
+                                   the blocking gss_step hop by hop (sample, mark, emit per hop).  1: visit-once also
+                                   in gss_step, 2: always hop by hop                                                   */
+  int32_t chain_workgroups;     /* visit-once steps: most workgroups of a chain phase, which stride over the hop's nodes
+                                   (1..65536; default 4096)                                                           */
+  int32_t reserved[6];          /* must be 0                                                                          */
 } gss_tuning;
 
 /* gss_create with the layout choices of `tuning` (NULL: all defaults, which is what gss_create passes). */

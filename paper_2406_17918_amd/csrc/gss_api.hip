@@ -87,6 +87,8 @@ struct Slot {
   int32_t* state_h = nullptr;            // pinned copy of the device state, written by the last emit phase
   int32_t* state_h_dev = nullptr;        // the same memory as the device sees it
   Buf hash, direct, picks, order, ranks, partial_first, partial_edge, first_off, edge_off;
+  Buf visit, held, list, counts;         // visit-once steps: visit table (8 bytes per node), holding area, node lists and their counters
+  int chain_parity = 0;                  // which of the two counter sets the slot's next visit-once step uses
   uint32_t ver = VERSION_FIRST;          // next unused dedupe table version
   Buf src_nodes[GSS_MAX_LAYERS][GSS_MAX_NODE_TYPES];
   Buf src_local[GSS_MAX_LAYERS][GSS_MAX_RELATIONS], dst_local[GSS_MAX_LAYERS][GSS_MAX_RELATIONS];
@@ -108,6 +110,8 @@ struct Slot {
   int table_set = 0;                     // FCR: the set of tables the step reads
   StepItems items;                       // the step's phases in order, and how many of them have been put into a tick
   uint32_t insert_hops = 0;              // hops whose dedupe table inserts run as a phase of their own
+  bool chain = false;                    // a visit-once step (chain phases + place / mark / emit)
+  ChainArgs chain_args;                  // ... and what its chain phases share
   std::vector<gss_block_nodes> out_nodes;
   std::vector<gss_block_edges> out_edges;
 };
@@ -167,6 +171,10 @@ struct gss_sampler {
   int dense_policy = 0;                  // gss_tuning.tick_build - 0: launches of DENSE_TICK_WGS workgroups and more use the dense build; 1: all, 2: none
   uint32_t first_version = VERSION_FIRST;   // where a slot's dedupe-table version counter starts
   int tick_cap = 1;                      // slices one launch can carry
+  int chain_wg_cap = 4096;               // most workgroups of a chain slice, which stride over the rest (the 4,096-seed workload: 2,048 +5 %, 8,192 +5 %)
+  bool visit_once_forced = false;        // gss_tuning.visit_once == 1: also the steps of blocking calls
+  bool blocking_call = false;            // inside gss_step
+  bool visit_once = false;               // steps run as visit-once steps where their size allows (SHARED_OTF on one relation)
   RelConst relc_h[GSS_MAX_RELATIONS] = {};   // per relation constants: host copy and device copy
   RelConst* relc_d = nullptr;
   SlotConst slotc_h[GSS_MAX_IN_FLIGHT] = {};   // per slot: the scratch pointers all phases of its step share; host copy and
@@ -176,7 +184,7 @@ struct gss_sampler {
   // kernels stride over whatever the frontier turns out to be, so a wrong guess only costs time.
   float fill_ratio[GSS_MAX_LAYERS];
   Slot slot[GSS_MAX_IN_FLIGHT];
-  HopParams tick_all[GSS_MAX_IN_FLIGHT], tick_launch[TICK_MAX_SLICES];   // scratch of tick(): slices of a tick, and of one launch
+  HopParams tick_all[2 * GSS_MAX_IN_FLIGHT], tick_launch[TICK_MAX_SLICES];   // scratch of tick(): slices of a tick, and of one launch
   hipEvent_t tick_ev[TICK_EVENTS] = {};  // completion events of the ticks in which steps finish, used round-robin
   int tick_ev_next = 0;
   int steps_per_tick = 1, unlaunched = 0; // steps enqueued since the last tick
@@ -347,6 +355,12 @@ void fill_slice(gss_sampler* s, Slot& sl, int it, HopParams& P) {
   P.partial_first = sc.partial_first; P.partial_edge = sc.partial_edge;
   P.first_off = sc.first_off; P.edge_off = sc.edge_off;
   P.slot = (int32_t)(&sl - s->slot);
+  if (sl.chain) {               // visit-once step: the place phase reads the hop's picks from the holding area
+    if (P.phase == PH_PLACE) {
+      P.visit = (const uint64_t*)sl.visit.p;
+      P.held = (const int32_t*)sl.held.p + sl.chain_args.off[h];
+    }
+  }
   int64_t max_f = 1;
   for (int t = 0; t < T; ++t) {
     TypeParam& tp = P.type[t];
@@ -388,7 +402,7 @@ void fill_slice(gss_sampler* s, Slot& sl, int it, HopParams& P) {
     P.gxd = (P.gx + 31) / 32; P.gyd = T;         // per node type: a thread per frontier node
   } else if (P.phase == PH_SCAN) {
     P.gx = 1; P.gy = 1;
-  } else {                                     // insert, mark, emit: tiles
+  } else {                                     // insert, place, mark, emit: tiles
     const int64_t tiles = (int64_t)(expect * (double)P.num_tiles_ub) + R;
     // (one workgroup per expected live tile, also on very large hops: with a cap of 1,024 workgroups, each walking
     // over several tiles, steps of 65,536 seeds were 7 % slower, of 262,144 seeds 11 %.  On graphs with several
@@ -400,7 +414,41 @@ void fill_slice(gss_sampler* s, Slot& sl, int it, HopParams& P) {
     if (P.scan_in_emit) gx = std::max<int64_t>(gx, (P.num_tiles_ub + EMIT_OWN_TILES - 1) / EMIT_OWN_TILES);
     P.gx = (int32_t)gx;
     P.gy = 1;
+    if (P.phase == PH_PLACE) {                 // ... and a row of workgroups with a thread per dst node
+      const int64_t nodes = std::min<int64_t>((int64_t)(expect * (double)max_f) + 8, max_f);
+      P.gxd = (int32_t)std::max<int64_t>((nodes + 255) / 256, 1);
+      P.gyd = 1;
+    }
   }
+}
+
+// Kernel arguments of chain phase c of the visit-once step held by `sl`.
+void fill_chain_slice(gss_sampler* s, Slot& sl, int c, HopParams& P) {
+  memset(static_cast<void*>(&P), 0, sizeof P);
+  const ChainArgs& C = sl.chain_args;
+  P.phase = PH_CHAIN;
+  P.R = 1; P.T = 1; P.hop = c; P.f = C.f(c); P.k = s->k; P.S = s->S;
+  P.n_new = s->n_new; P.mode = (int)s->mode; P.refresh_now = sl.refresh_now ? 1 : 0;
+  P.step = (uint32_t)sl.step;
+  P.layer_word = 0xFFu; P.shared = 1; P.layer = sl.L - 1 - c;
+  P.seed_lo = (uint32_t)(s->seed & 0xffffffffu);
+  P.seed_hi = (uint32_t)(s->seed >> 32);
+  P.state = sl.state_d;
+  P.state_words = s->state_words;
+  P.slot = (int32_t)(&sl - s->slot);
+  P.ver = sl.ver0 + (uint32_t)c;
+  P.type[0].frontier = sl.seeds;
+  P.type[0].key_off = s->key_off[0];
+  P.type[0].n_nodes = (int32_t)s->num_nodes[0];
+  P.type[0].count_override = sl.num_seeds;
+  P.type[0].frontier_cap = sl.num_seeds;
+  P.rel[0].table = s->table[sl.table_set][0][0];
+  // one 32-lane group per node of hop c's frontier (sized by what recent steps filled of the host-known bound), eight
+  // groups per workgroup, which stride over the rest
+  int64_t groups = sl.num_seeds;
+  if (c > 0) groups = std::min<int64_t>((int64_t)(std::min(1.0, 1.1 * (double)s->fill_ratio[c]) * (double)sl.fub[c][0]) + 8, sl.fub[c][0]);
+  P.gx = (int32_t)std::min<int64_t>(std::max<int64_t>((groups + 7) / 8, 1), s->chain_wg_cap);
+  P.gy = 1;
 }
 
 // One tick: the next phase of every step in flight that may run now (oldest first), in as few launches
@@ -416,10 +464,10 @@ gss_status tick(gss_sampler* s, int* issued) {
     Slot& sl = s->slot[(s->enq + q) % s->ring];
     if (sl.pending) { flight[nf] = &sl; items[nf++] = &sl.items; }
   }
-  int pick[GSS_MAX_IN_FLIGHT];
+  TickPick pick[2 * GSS_MAX_IN_FLIGHT];
   const int n = plan_tick(items, nf, s->otf, s->shared, pick);
-  Slot* take[GSS_MAX_IN_FLIGHT];
-  for (int i = 0; i < n; ++i) take[i] = flight[pick[i]];
+  Slot* take[2 * GSS_MAX_IN_FLIGHT];
+  for (int i = 0; i < n; ++i) take[i] = flight[pick[i].step];
   if (issued) *issued = n;
   // Workgroups start in grid order, and the chip holds about as many as a full tick has.  The slices with few
   // workgroups (mark / emit of the inner hops, the inner sample phases) are the long dependent chains that decide when
@@ -428,16 +476,24 @@ gss_status tick(gss_sampler* s, int* issued) {
   // a full tick of the 1,024-seed FCR workload 16.5 instead of 23.5 us, of the OTF ones 3-5 % less).
   HopParams* all = s->tick_all;          // (tens of KB: kept in the handle, not on the caller's stack)
   HopParams* P = s->tick_launch;
-  int order[GSS_MAX_IN_FLIGHT];
-  for (int i = 0; i < n; ++i) { fill_slice(s, *take[i], take[i]->items.next_item, all[i]); order[i] = i; }
+  int order[2 * GSS_MAX_IN_FLIGHT];
+  const ChainArgs* chain = nullptr;      // of the tick's chain phase (chain phases of different steps never share a tick)
+  for (int i = 0; i < n; ++i) {
+    if (pick[i].item >= 0) fill_slice(s, *take[i], pick[i].item, all[i]);
+    else { fill_chain_slice(s, *take[i], -1 - pick[i].item, all[i]); chain = &take[i]->chain_args; }
+    order[i] = i;
+  }
   auto weight = [&](int i) { return all[i].gx * all[i].gy + all[i].gxd * all[i].gyd; };
-  std::sort(order, order + n, [&](int a, int b) { return weight(a) < weight(b); });
+  // (a chain slice - the phase the next step waits for - leads the grid whatever its width: the 4,096-seed workload
+  // with the shared table -8 % per step)
+  auto rank_of = [&](int i) { return all[i].phase == PH_CHAIN ? -1 : weight(i); };
+  std::sort(order, order + n, [&](int a, int b) { return rank_of(a) < rank_of(b); });
   // A step whose last phase (an emit phase, which writes its counts + error flag into pinned host memory) is in
   // this tick is done when the tick's last launch is: that launch completes the step's `done` event itself.
   // (Several steps may end with one tick: they share its event.)
   hipEvent_t done = nullptr;
   for (int i = 0; i < n; ++i)
-    if (take[i]->items.next_item + 1 == take[i]->items.num_items) {
+    if (pick[i].item >= 0 && pick[i].item + 1 == take[i]->items.num_items) {
       if (!done) { done = s->tick_ev[s->tick_ev_next]; s->tick_ev_next = (s->tick_ev_next + 1) % TICK_EVENTS; }
       take[i]->done = done;
     }
@@ -452,10 +508,12 @@ gss_status tick(gss_sampler* s, int* issued) {
     // size, 1-4 % per step on the 1,024-seed workload; FBL and OTF fetch, which draw from the adjacency, lose 2-7 %)
     const bool rows_only = s->fcr && !s->shared && s->theta < 0;
     const bool dense = s->dense_policy == 1 || (s->dense_policy == 0 && (rows_only || wgs >= DENSE_TICK_WGS));
-    hipError_t e = launch_tick(P, m, s->relc_h, s->relc_d, s->slotc_d, s->work, s->timer, last ? done : nullptr, dense);
+    hipError_t e = launch_tick(P, m, s->relc_h, s->relc_d, s->slotc_d, s->visit_once, chain, s->work, s->timer, last ? done : nullptr, dense);
     if (e != hipSuccess) { s->poisoned = true; return fail(s, GSS_ERR_DEVICE, "launch: %s", hipGetErrorString(e)); }
   }
-  for (int i = 0; i < n; ++i) ++take[i]->items.next_item;
+  for (int i = 0; i < n; ++i) {
+    if (pick[i].item >= 0) ++take[i]->items.next_item; else ++take[i]->items.next_chain;
+  }
   return GSS_OK;
 }
 
@@ -512,7 +570,7 @@ void destroy_impl(gss_sampler* s) {
       for (int q = 0; q < GSS_MAX_NODE_TYPES; ++q) release(s, sl.src_nodes[t][q]);
     }
     Buf* bufs[] = {&sl.hash, &sl.direct, &sl.picks, &sl.order, &sl.ranks, &sl.partial_first, &sl.partial_edge,
-                   &sl.first_off, &sl.edge_off};
+                   &sl.first_off, &sl.edge_off, &sl.visit, &sl.held, &sl.list, &sl.counts};
     for (Buf* b : bufs) release(s, *b);
     dev_free(s, sl.state_d);
     if (sl.state_h) (void)hipHostFree(sl.state_h);
@@ -571,7 +629,7 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   if (tn.dedupe_layout < 0 || tn.dedupe_layout > 2 || tn.table_sets < 0 || tn.table_sets > MAX_TABLE_SETS ||
       tn.pipeline_depth < 0 || tn.pipeline_depth > GSS_MAX_IN_FLIGHT || tn.steps_per_tick < 0 || tn.steps_per_tick > 2 ||
       tn.insert_phase < 0 || tn.insert_phase > 2 || tn.scan_phase < 0 || tn.scan_phase > 1 || tn.tick_build < 0 ||
-      tn.tick_build > 2 || tn.first_dedupe_version >= VERSION_LAST)
+      tn.tick_build > 2 || tn.visit_once < 0 || tn.visit_once > 2 || tn.chain_workgroups < 0 || tn.chain_workgroups > 65536 || tn.first_dedupe_version >= VERSION_LAST)
     return early(GSS_ERR_INVALID_ARG, "invalid argument (tuning field out of range)");
   for (int32_t v : tn.reserved)
     if (v != 0) return early(GSS_ERR_INVALID_ARG, "invalid argument (tuning: reserved fields must be 0)");
@@ -627,6 +685,12 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   s->dense_policy = tn.tick_build;
   s->first_version = tn.first_dedupe_version ? tn.first_dedupe_version : VERSION_FIRST;
   s->tick_cap = tick_capacity(s->R, s->T);
+  // One table for all hops and a refresh per visit: the steps run as visit-once steps (chain phases) where the graph
+  // has one relation; all its launches use the build of the step kernel that holds the chain's code and arguments.
+  s->visit_once = c->mode == GSS_MODE_SHARED_OTF && s->R == 1 && s->T == 1 && tn.visit_once != 2;
+  if (s->visit_once) s->tick_cap = CHAIN_TICK_SLICES;
+  if (tn.chain_workgroups) s->chain_wg_cap = tn.chain_workgroups;
+  s->visit_once_forced = tn.visit_once == 1;
   for (float& r : s->fill_ratio) r = 1.0f;
   // Dedupe table layout: one 8-byte word per node (no probing, one atomic per insert) unless that
   // would be large; gss_tuning.dedupe_layout overrides the choice.
@@ -652,6 +716,8 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   // caller waits for has left the queue before.  (Deeper rings only widen the memory the launches touch: every slot
   // has scratch and a dedupe table of its own - 4 L + 4 was 1 % slower on the 1,024-seed workloads, 4 L too shallow.)
   s->ring = std::min(GSS_MAX_IN_FLIGHT, s->steps_per_tick * (4 * s->L + 2));
+  // (a visit-once step of L hops is in flight for about 4 L launches, of which L are its own: L + 3 steps cover that)
+  if (s->visit_once) s->ring = std::min(GSS_MAX_IN_FLIGHT, s->L + 3);
   if (tn.pipeline_depth) s->ring = tn.pipeline_depth;
   if ((e = hipStreamCreateWithFlags(&s->work, hipStreamNonBlocking)) != hipSuccess) { s->work = nullptr; return hipfail(e); }
   for (hipEvent_t& ev : s->tick_ev)
@@ -835,6 +901,23 @@ static gss_status grow_slot(gss_sampler* s, Slot& sl, const Slot& plan, int L, i
           !need(sl.dst_local[l][r], sizeof(int32_t) * (size_t)std::max<int64_t>(plan.slots_ub[h][r], 1)))
         return fail(s, GSS_ERR_OOM, "step: output allocation failed");
   }
+  if (plan.chain) {
+    const ChainArgs& C = plan.chain_args;
+    if (!sl.visit.p) {
+      if (!need(sl.visit, sizeof(uint64_t) * (size_t)std::max<int64_t>(s->total_nodes, 1)))
+        return fail(s, GSS_ERR_OOM, "step: visit table allocation failed");
+      HIP_TRY(s, hipMemsetAsync(sl.visit.p, 0xFF, sl.visit.bytes, st));
+    }
+    const size_t held = (size_t)C.off[L - 1] + (size_t)C.V[L - 1] * C.f(L - 1);
+    if (!need(sl.held, sizeof(int32_t) * std::max<size_t>(held, 1))) return fail(s, GSS_ERR_OOM, "step: holding area allocation failed");
+    size_t entries = 0;
+    for (int h = 1; h < L; ++h) entries = (size_t)C.loff[h] + (size_t)CHAIN_SEGS * C.lcap[h];
+    if (!need(sl.list, sizeof(uint64_t) * std::max<size_t>(entries, 1))) return fail(s, GSS_ERR_OOM, "step: node list allocation failed");
+    if (!sl.counts.p) {
+      if (!need(sl.counts, sizeof(uint32_t) * 2 * CHAIN_MAX_HOPS * CHAIN_SEGS * CHAIN_COUNT_STRIDE)) return fail(s, GSS_ERR_OOM, "step: node list allocation failed");
+      HIP_TRY(s, hipMemsetAsync(sl.counts.p, 0, sl.counts.bytes, st));
+    }
+  }
   // the slot's entry of the device table follows its buffers (they only change while they grow)
   const int idx = (int)(&sl - s->slot);
   const SlotConst sc = slot_const(s, sl);
@@ -888,6 +971,33 @@ gss_status gss_step_async(gss_sampler* s, const int32_t* seeds, int32_t num_seed
     max_keys = std::max(max_keys, keys);
   }
   if (max_slots >= (int64_t(1) << 31)) return fail(s, GSS_ERR_INVALID_ARG, "step: batch too large (pick slots >= 2^31)");
+  // ---- visit-once step?  Its holding index space is laid out by bounds that are not capped by the number of nodes:
+  //      V[h+1] = V[h] * (1 + f[h]).  Steps whose holding area would pass 2^28 picks (1 GiB) run the per-hop way. ----
+  ChainArgs chain_args;
+  memset(static_cast<void*>(&chain_args), 0, sizeof chain_args);
+  // (a blocking gss_step has the launches to itself: hop by hop it needs one fewer, and none of them carries two phases)
+  bool chain = s->visit_once && L <= CHAIN_MAX_HOPS && !(s->blocking_call && !s->visit_once_forced);
+  if (chain) {
+    int64_t V = num_seeds, off = 0, band = 0;
+    int64_t band_of[GSS_MAX_LAYERS] = {};
+    for (int l = 0; l < L; ++l) { band_of[l] = band; band += fanouts[l]; }   // layer l's band starts at the sum of the lower layers' fanouts
+    for (int h = 0; h < L && chain; ++h) {
+      const int f = fanouts[L - 1 - h];
+      chain_args.V[h] = (int32_t)V; chain_args.off[h] = (uint32_t)off;
+      chain_args.fbl[h] = (uint32_t)f | ((uint32_t)band_of[L - 1 - h] << 8) | ((uint32_t)(L - 1 - h) << 16);
+      // list h + 1: CHAIN_SEGS segments, each for the picks of every CHAIN_SEGS-th pair of hop h's frontier nodes
+      if (h + 1 < L) {
+        const int64_t cap = ((V + 1) / 2 + CHAIN_SEGS - 1) / CHAIN_SEGS * 2 * f;
+        chain_args.loff[h + 1] = chain_args.loff[h] + (h ? (uint32_t)CHAIN_SEGS * chain_args.lcap[h] : 0u);
+        chain_args.lcap[h + 1] = (uint32_t)cap;
+        if (cap * CHAIN_SEGS >= (int64_t(1) << 28)) chain = false;
+      }
+      off += V * f;
+      V += V * f;
+      if (off >= (int64_t(1) << 28)) chain = false;
+    }
+    chain_args.L = L;
+  }
 
   hipStream_t st = s->work;
   // ---- OTF: hops of steps with different layer counts would meet on the same per-layer table in one
@@ -922,6 +1032,8 @@ gss_status gss_step_async(gss_sampler* s, const int32_t* seeds, int32_t num_seed
   //      step yet: the allocations of a run then all happen at its first step, not once per slot as the ring is first
   //      walked.  (A slot that has held a step keeps its buffers until it is used again: the caller may still be
   //      reading that step's blocks.) ----
+  sl.chain = chain;
+  sl.chain_args = chain_args;
   {
     bool grew = false;
     gss_status gs = grow_slot(s, sl, sl, L, max_slots, max_keys, st, &grew);
@@ -933,9 +1045,18 @@ gss_status gss_step_async(gss_sampler* s, const int32_t* seeds, int32_t num_seed
         if ((gs = grow_slot(s, o, sl, L, max_slots, max_keys, st, nullptr)) != GSS_OK) return gs;
       }
   }
+  if (chain) {
+    sl.chain_args.held = (int32_t*)sl.held.p;
+    sl.chain_args.visit = (uint64_t*)sl.visit.p;
+    sl.chain_args.list = (uint64_t*)sl.list.p;
+    sl.chain_args.counts = (uint32_t*)sl.counts.p + sl.chain_parity * CHAIN_MAX_HOPS * CHAIN_SEGS * CHAIN_COUNT_STRIDE;
+    sl.chain_args.counts_next = (uint32_t*)sl.counts.p + (1 - sl.chain_parity) * CHAIN_MAX_HOPS * CHAIN_SEGS * CHAIN_COUNT_STRIDE;
+    sl.chain_parity ^= 1;
+  }
   if (sl.ver + (uint32_t)L >= VERSION_LAST) {        // version space exhausted: start over with a clean table
     if (s->use_direct) HIP_TRY(s, hipMemsetAsync(sl.direct.p, 0xFF, sl.direct.bytes, st));
     else HIP_TRY(s, hipMemsetAsync(sl.hash.p, 0xFF, sl.hash.bytes, st));
+    if (sl.visit.p) HIP_TRY(s, hipMemsetAsync(sl.visit.p, 0xFF, sl.visit.bytes, st));
     sl.ver = VERSION_FIRST;
   }
   s->last_step = step;
@@ -958,14 +1079,14 @@ gss_status gss_step_async(gss_sampler* s, const int32_t* seeds, int32_t num_seed
   sl.insert_hops = 0;
   int phases = 3 * L;
   for (int h = 0; h < L; ++h) phases += scans_in_emit(s, sl, h) ? 0 : 1;
-  for (int h = L - 1; h >= 0; --h) {           // the outermost hop is the widest
+  for (int h = L - 1; h >= 0 && !chain; --h) {           // the outermost hop is the widest
     const double expect = std::min(1.0, 1.25 * (double)s->fill_ratio[h]) * (double)sl.total_slots[h];
     const bool wide = !s->otf && expect >= (double)INSERT_SPLIT_SLOTS;
     const bool narrow = !(s->otf && s->shared) && expect <= (double)INSERT_SMALL_SLOTS;
     const bool split = s->insert_policy == 1 || (s->insert_policy == 0 && phases < s->tick_cap && (wide || narrow));
     if (split) { sl.insert_hops |= 1u << h; ++phases; }
   }
-  sl.items.build(L, scan_hops, sl.insert_hops);
+  sl.items.build(L, scan_hops, sl.insert_hops, chain);
 
   // ---- Alg. 3: full refresh when the refresh epoch changes, into the set of tables that is not in use
   //      (stream order puts it after the steps that last read that set: their phases are all issued) ----
@@ -1058,7 +1179,9 @@ gss_status gss_step(gss_sampler* s, const int32_t* seeds, int32_t num_seeds, int
   if (!s || !out) return GSS_ERR_INVALID_ARG;
   if (oldest_pending(s))
     return fail(s, GSS_ERR_INVALID_ARG, "step: collect the steps in flight with gss_step_wait first");
+  s->blocking_call = true;
   gss_status st = gss_step_async(s, seeds, num_seeds, seed_type, fanouts, num_layers, step);
+  s->blocking_call = false;
   if (st != GSS_OK) return st;
   return gss_step_wait(s, out);
 }

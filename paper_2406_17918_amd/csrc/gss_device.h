@@ -77,8 +77,16 @@ struct HopCommon {
   uint32_t* ranks;          // [slots] rank among firsts (lo 16) / among edges (hi 16) within the tile
   int32_t* partial_first;   // [tiles]
   int32_t* partial_edge;
-  int32_t* first_off;
-  int32_t* edge_off;
+  union {
+    struct {                // scan and emit phases
+      int32_t* first_off;
+      int32_t* edge_off;
+    };
+    struct {                // place phase of a visit-once step: the hop's part of the holding area, the step's visit
+      const int32_t* held;  // table (node -> holding index, see ChainArgs)
+      const uint64_t* visit;
+    };
+  };
   int32_t phase;            // Phase
   int32_t gx, gy, gxd, gyd; // the slice's workgroups: gy rows of gx, then gyd rows of gxd
   int32_t R, T;
@@ -89,6 +97,43 @@ struct HopCommon {
   int32_t shared, layer;        // shared: one table for all layers, per-layer rank bands; layer: l of this hop
   int32_t insert_split, slot;   // the hop has an insert phase: the sample phase leaves the picks' table inserts to it; slot: the step's slot
   uint32_t ver, step, layer_word, seed_lo, seed_hi;
+  // (visit-once steps: the version of the step's visit table entries is that of its hop 0 dedupe entries)
+  __host__ __device__ uint32_t visit_ver() const { return ver - (uint32_t)hop; }
+};
+// Visit-once steps (one table for all hops, refreshed per visit, one relation).  The chain phase of hop c visits the nodes
+// that hop c reaches for the first time in this step and draws, from the node's one (refreshed) row, the picks of ALL its
+// remaining hops c .. L-1.  A visited node gets a "holding index" Q: seeds Q = seed index; a node first reached through
+// pick j of hop c-1 of the node with index Qp: Q = V[c-1] + Qp * f[c-1] + j, with V[0] = number of seeds and
+// V[h+1] = V[h] * (1 + f[h]) - an index space with holes, laid out by host-known bounds.  The picks of hop h of node
+// Q are held at held[off[h] + Q * f[h] + 0 .. f[h]) (picks first, then -1).
+//   visit[v]       = (~ver << 32) | Q, claimed with a compare-and-swap: whichever pick comes first visits the node
+//   list h >= 1    the nodes first reached by hop h, as (Q << 32) | v, appended by the chain phase of hop h-1 while it
+//                  looks up its own hop's picks.  CHAIN_SEGS segments with a counter each (appends to one counter would
+//                  serialise); the pair of nodes a wavefront works on appends to segment (item index / 2) % CHAIN_SEGS,
+//                  so a segment of list h+1 holds at most ceil(V[h] / (2 CHAIN_SEGS)) * 2 * f[h] entries.
+// The counters come in two sets: a step's first chain phase clears the set that the slot's next step will use.
+// Nothing here decides an output order: the place / mark / emit phases do that from the frontier, exactly as for
+// other steps.  Which of several picks of a node claims it only decides the node's Q and list position, which no
+// output shows.
+constexpr int CHAIN_MAX_HOPS = 4;
+constexpr int CHAIN_SEGS = 32;
+constexpr int CHAIN_COUNT_STRIDE = 32;       // words between two counters: one 128-byte line each (atomics on one line serialise)
+constexpr int CHAIN_TICK_SLICES = 8;        // most slices of a launch of the build that runs visit-once steps
+struct ChainArgs {
+  int32_t* held;
+  uint64_t* visit;
+  uint64_t* list;
+  uint32_t* counts;                   // [CHAIN_MAX_HOPS][CHAIN_SEGS] of this step, CHAIN_COUNT_STRIDE words apart
+  uint32_t* counts_next;              // the other set
+  uint32_t off[CHAIN_MAX_HOPS];       // start of hop h's picks in `held`
+  int32_t V[CHAIN_MAX_HOPS];          // size of hop h's holding index space
+  uint32_t loff[CHAIN_MAX_HOPS];      // start of list h in `list`
+  uint32_t lcap[CHAIN_MAX_HOPS];      // entries a segment of list h can hold
+  uint32_t fbl[CHAIN_MAX_HOPS];       // per hop: fanout | first rank of its band << 8 | layer << 16 (whole words: the
+  int32_t L;                          // kernel reads its arguments with scalar loads, which have no byte form)
+  __host__ __device__ int f(int h) const { return (int)(fbl[h] & 0xFFu); }
+  __host__ __device__ int band(int h) const { return (int)((fbl[h] >> 8) & 0xFFu); }
+  __host__ __device__ uint32_t layer(int h) const { return (fbl[h] >> 16) & 0xFFu; }
 };
 // Kernel arguments are limited to 4 KB, so the relation / node type arrays come in three sizes.
 template <int MAXR, int MAXT>
@@ -118,8 +163,14 @@ struct HopParamsSmall : HopCommon {
 };
 using HopParams = HopParamsT<GSS_MAX_RELATIONS, GSS_MAX_NODE_TYPES>;
 using HopParamsMid = HopParamsT<8, 4>;
+// (Samplers that run visit-once steps use a build of the step kernel of their own, whose launches carry the arguments
+// of a chain slice - at most one each, as chain phases of different steps never share a launch.  The other builds
+// hold none of that code: it costs them registers.)
+struct HopParamsChain : HopParamsMono {};     // the same slice in a launch that also carries a chain's arguments
+template <class HP> struct ChainOf { static constexpr bool HAS_CHAIN = false; };
+template <> struct ChainOf<HopParamsChain> { static constexpr bool HAS_CHAIN = true; ChainArgs chain; };
 template <class HP, int D>
-struct TickT {
+struct TickT : ChainOf<HP> {
   using Slice = HP;
   static constexpr int SLICES = D;
   HP s[D];
@@ -202,9 +253,11 @@ hipError_t launch_list_from_map(const int32_t* map, int64_t n, int32_t* list, hi
 // One tick: a single launch over n <= tick_capacity slices.  `relc_host` / `relc_dev`: the R RelConst records
 // (host copy, device copy).  `done`, if non-null, completes when the launch has.  `dense`: use the build of the kernel
 // that fits eight workgroups on a CU instead of seven (for launches of several times the chip's capacity; the compact
-// launch of one-relation graphs has no such build).
+// launch of one-relation graphs has no such build).  `chain_build`: the sampler runs visit-once steps (one relation; at
+// most CHAIN_TICK_SLICES slices per launch); `chain`: the arguments of the launch's chain slice, if it has one.
 hipError_t launch_tick(const HopParams* slices, int n, const RelConst* relc_host, const RelConst* relc_dev,
-                       const SlotConst* slots_dev, hipStream_t st, LaunchTimer* timer, hipEvent_t done, bool dense);
+                       const SlotConst* slots_dev, bool chain_build, const ChainArgs* chain, hipStream_t st, LaunchTimer* timer,
+                       hipEvent_t done, bool dense);
 hipError_t launch_validate_graph(const void* indptr, int is64, int64_t n_dst, const int32_t* indices, int64_t nnz,
                                  int64_t n_src, int32_t* state, hipStream_t st);
 hipError_t launch_cache_read(const int32_t* table, const int32_t* row_of, int64_t n, int k, int S, int32_t* out,

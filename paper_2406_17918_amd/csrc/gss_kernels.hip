@@ -17,6 +17,7 @@
 #include <hip/hip_ext.h>
 
 #include <cstring>
+#include <type_traits>
 
 #include "gss_device.h"
 
@@ -71,6 +72,7 @@ __device__ __forceinline__ uint32_t below(uint64_t x64, uint32_t m) {
   const uint64_t u = (x64 >> 32) * m + (t >> 32);
   return (uint32_t)(u >> 32);
 }
+constexpr int ITEMS_PER_THREAD = TILE / TILE_THREADS;   // consecutive pick slots a thread of a tile phase owns
 constexpr uint64_t PRIO_NONE = ~0ull;   // larger than every real priority (their low 16 bits are < 64)
 
 __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63u); }
@@ -516,19 +518,25 @@ __device__ __forceinline__ LiveTile live_tile(const HP& P, const LiveLds* L, int
 //               rows wg.y >= R: node type y-R, one thread per frontier node (insert the dst
 //               nodes into the dedupe table with order = frontier index, copy them to src_nodes).
 // ------------------------------------------------------------------------------------------
+// Node type t of a hop, one thread per frontier node: the dst nodes enter the dedupe table (order = frontier index)
+// and head the hop's src_nodes.  Workgroup x of the P.gxd that share the work.
+template <class HP>
+__device__ __forceinline__ void dst_node_rows(const HP& P, int t, int x) {
+  const TypeParam& TP = type_of(P, t);
+  const int F = frontier_count(P, t);
+  for (int i = x * (int)blockDim.x + (int)threadIdx.x; i < F; i += P.gxd * (int)blockDim.x) {
+    const int v = TP.frontier[i];
+    if ((uint32_t)v >= (uint32_t)TP.n_nodes) { atomicOr(&P.state[ST_ERROR], ERR_SEED_RANGE); continue; }
+    TP.src_nodes[i] = v;
+    const uint32_t old = table_insert_min(P.ht, P.ver, TP.key_off + (uint32_t)v, (uint32_t)i, P.state);
+    if (old < EDGE_BIT && old != (uint32_t)i) atomicOr(&P.state[ST_ERROR], ERR_SEED_DUP);
+  }
+}
+
 template <class HP>
 __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLds* lds) {
   if (wg.y >= P.R) {
-    const int t = wg.y - P.R;
-    const TypeParam& TP = type_of(P, t);
-    const int F = frontier_count(P, t);
-    for (int i = wg.x * (int)blockDim.x + (int)threadIdx.x; i < F; i += P.gxd * (int)blockDim.x) {
-      const int v = TP.frontier[i];
-      if ((uint32_t)v >= (uint32_t)TP.n_nodes) { atomicOr(&P.state[ST_ERROR], ERR_SEED_RANGE); continue; }
-      TP.src_nodes[i] = v;
-      const uint32_t old = table_insert_min(P.ht, P.ver, TP.key_off + (uint32_t)v, (uint32_t)i, P.state);
-      if (old < EDGE_BIT && old != (uint32_t)i) atomicOr(&P.state[ST_ERROR], ERR_SEED_DUP);
-    }
+    dst_node_rows(P, wg.y - P.R, wg.x);
     return;
   }
   Grp G;
@@ -671,6 +679,243 @@ __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLds*
       if (!P.insert_split) table_insert_min(P.ht, P.ver, src_key_off + (uint32_t)val, EDGE_BIT | g, P.state);
     }
     if (sub >= cnt && sub < f) P.picks[g0 + sub] = -1;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Visit-once steps (see ChainArgs): chain phase and place phase.
+// ------------------------------------------------------------------------------------------
+// Marks node v as visited in this step with holding index Q (`mine` = (~version << 32) | Q).  True for exactly one
+// of the picks that name the same node in one step.
+__device__ __forceinline__ bool claim_visit(uint64_t* visit, uint32_t v, uint64_t mine) {
+  unsigned long long* w = (unsigned long long*)&visit[v];
+  const uint64_t cur = __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if ((uint32_t)(cur >> 32) == (uint32_t)(mine >> 32)) return false;      // visited already
+  // (a word of another version can only turn into one of this step's version)
+  return atomicCAS(w, (unsigned long long)cur, (unsigned long long)mine) == cur;
+}
+// The same for a seed (holding index Q < num_seeds).  A seed must be visited as a seed even if a pick of another seed
+// names it and claims it before its own group gets to it: words of later versions and smaller indices are smaller, so an
+// atomic minimum lets the seed take the entry over (the pick's entry in list 1 then points at an index the visit table
+// no longer holds, and is skipped).
+__device__ __forceinline__ void claim_seed(uint64_t* visit, uint32_t v, uint64_t mine) {
+  __hip_atomic_fetch_min((unsigned long long*)&visit[v], (unsigned long long)mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The one visit of node v in this step, by the hop c that reaches it first: read the row, refresh it when the step
+// refreshes (Alg. 2 RefreshCache on the shared table: once per node and step), rank the slots once by PICK priority,
+// and take for every hop h = c .. L-1 the ranks [band[h], band[h] + f[h]) ("Shared Cache Design": per-layer bands of
+// one per-(step, node) ranking) - what the per-hop sample phase computes when it meets the node again in hop h.
+// Nodes without a cache row (degree split) draw every hop straight from the adjacency, keyed by the hop's layer.
+// Returns hop c's pick number `sub` (-1 beyond the node's picks).
+template <class HP>
+__device__ __forceinline__ int visit_node(const HP& P, const ChainArgs& C, const Grp& G, int c, int v, uint32_t Q) {
+  const RelParam& RP = rel_of(P, 0);
+  const RelConst& RC = P.rc(0);
+  const int k = P.k, sub = G.sub;
+  DrawKey K{P.seed_lo, P.seed_hi, (uint32_t)v, P.step, P.layer_word << 8};
+  int at = v;
+  int64_t b = 0, d64 = 0;
+  if (RC.row_of) at = RC.row_of[v];
+  if (RC.row_of || P.refresh_now) {
+    b = load_indptr(RC.indptr, RC.is64, v);
+    d64 = load_indptr(RC.indptr, RC.is64, (int64_t)v + 1) - b;
+  }
+  int mine = -1;
+  if (at < 0) {
+    for (int h = c; h < C.L; ++h) {
+      const int f = C.f(h);
+      K.tag = C.layer(h) << 8;
+      int val = grp_fill_full_row(G, RC.indices + b, (uint32_t)d64, f, K, P_FBL, P.state);
+      const int cnt = (int)(d64 < f ? d64 : (int64_t)f);
+      if (sub >= cnt) val = -1;
+      if (sub < f) C.held[C.off[h] + Q * (uint32_t)f + (uint32_t)sub] = val;
+      if (h == c) mine = val;
+    }
+    return mine;
+  }
+  int32_t* row = RP.table + (int64_t)at * P.S;
+  int val = (sub < k) ? row[sub] : -1;
+  const int len = __popc(grp_ballot(G, val >= 0));
+  const bool refresh = P.refresh_now && len == k && d64 > k;
+  bool ranked = false;
+  for (int h = c; h < C.L; ++h) ranked |= len > C.f(h);
+  Block4 sb{0u, 0u, 0u, 0u};
+  if ((refresh || ranked) && sub < k) sb = draw_block(K, P_EVICT, (uint32_t)sub, 0);
+  if (refresh) {
+    uint32_t evict;
+    val = grp_refresh_part(G, val, k, P.n_new, sb, RC.indices + b, (uint32_t)d64, K, P.state, evict);
+    if ((evict >> sub) & 1u) row[sub] = val;
+  }
+  int rank = 0;
+  if (ranked) {
+    const uint64_t pp = (sub < len) ? priority(hi64(sb), (uint32_t)sub) : PRIO_NONE;
+    G.L->prio[sub] = pp;
+    rank = grp_rank(G, len, pp);
+  }
+  for (int h = c; h < C.L; ++h) {
+    const int f = C.f(h);
+    bool sel = sub < len;
+    if (len > f) {
+      const int start = min(C.band(h), len - f);
+      sel = sub < len && rank >= start && rank < start + f;
+    }
+    const uint32_t selm = grp_ballot(G, sel);
+    const int cnt = __popc(selm);
+    if (sel) G.L->out[__popc(selm & below_mask(sub))] = val;       // picks in slot order, through LDS
+    const int pick = (sub < cnt) ? G.L->out[sub] : -1;
+    if (sub < f) C.held[C.off[h] + Q * (uint32_t)f + (uint32_t)sub] = pick;
+    if (h == c) mine = pick;
+  }
+  return mine;
+}
+
+// chain phase of hop c: one 32-lane group per node of the frontier of hop c, eight groups per workgroup, striding.
+// The nodes that hop c reaches first - the seeds for c = 0, else list c - are visited.  Unless c is the last hop, hop
+// c's picks of every frontier node - of the ones just visited, and of the nodes of earlier hops, whose picks are held -
+// then claim their nodes: a pick that comes first appends its node to list c + 1.
+struct ChainLds { uint32_t start[CHAIN_MAX_HOPS * CHAIN_SEGS + 2]; };
+template <class HP>
+__device__ __forceinline__ void chain_phase(const HP& P, const ChainArgs& C, const Wg wg, GroupLds* lds, ChainLds* CL) {
+  Grp G;
+  G.sub = (int)(threadIdx.x & 31u);
+  G.half = (int)((threadIdx.x >> 5) & 1u);
+  G.L = (GroupLdsPtr)&lds[threadIdx.x >> 5];
+  const int c = P.hop, sub = G.sub, L = C.L;
+  const int grp = wg.x * (int)(blockDim.x >> 5) + (int)(threadIdx.x >> 5);
+  const int ngrp = P.gx * (int)(blockDim.x >> 5);
+  const RelConst& RC = P.rc(0);
+  const uint64_t vtag = (uint64_t)(~P.visit_ver()) << 32;
+  const uint32_t F0 = (uint32_t)C.V[0];
+  const bool claims = c + 1 < L;
+  // ---- the items: seeds (unless only list c has work to do), then the segments of lists 1 .. c ----
+  const int first_list = claims ? 0 : c;                 // the last hop only visits
+  const uint32_t nseeds = first_list == 0 ? F0 : 0u;
+  const int h0 = first_list > 1 ? first_list : 1;        // first list kept in segments
+  const int nsegs = c >= h0 ? (c - h0 + 1) * CHAIN_SEGS : 0;
+  if (c == 0 && wg.x == 0 && threadIdx.x < CHAIN_MAX_HOPS * CHAIN_SEGS) C.counts_next[threadIdx.x * CHAIN_COUNT_STRIDE] = 0u;
+  if (nsegs > 0) {
+    if ((int)threadIdx.x < nsegs) {
+      const uint32_t n = C.counts[(h0 * CHAIN_SEGS + (int)threadIdx.x) * CHAIN_COUNT_STRIDE];
+      const uint32_t cap = C.lcap[h0 + (int)threadIdx.x / CHAIN_SEGS];
+      if (n > cap) atomicOr(&P.state[ST_ERROR], ERR_TABLE_FULL);
+      CL->start[threadIdx.x + 1] = n < cap ? n : cap;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      uint32_t run = nseeds;
+      for (int q = 0; q < nsegs; ++q) { const uint32_t n = CL->start[q + 1]; CL->start[q] = run; run += n; }
+      CL->start[nsegs] = run;
+    }
+    __syncthreads();
+  }
+  const uint32_t total = nsegs > 0 ? CL->start[nsegs] : nseeds;
+  const int32_t* __restrict__ seeds = type_of(P, 0).frontier;
+  const int fc = C.f(c);
+  // item g -> the node: its id (seeds) or its list entry (Q << 32 | v), and the list it is in
+  auto item = [&](uint32_t g, int& h) -> uint64_t {
+    if (g < nseeds) { h = 0; return ((uint64_t)g << 32) | (uint32_t)seeds[g]; }
+    int q = 0;                                           // the segment that holds item g (start[] is ascending)
+    for (int step = 64; step > 0; step >>= 1)
+      if (q + step < nsegs && CL->start[q + step] <= g) q += step;
+    h = h0 + q / CHAIN_SEGS;
+    return C.list[C.loff[h] + (uint32_t)(q % CHAIN_SEGS) * C.lcap[h] + (g - CL->start[q])];
+  };
+  int h_ahead = 0;
+  uint64_t e_ahead = (uint32_t)grp < total ? item((uint32_t)grp, h_ahead) : 0ull;
+  for (uint32_t g = (uint32_t)grp; g < total; g += (uint32_t)ngrp) {
+    // ---- which node (the group's next item travels while this one is worked on) ----
+    const uint64_t e = e_ahead;
+    const int h = h_ahead;
+    if (g + (uint32_t)ngrp < total) e_ahead = item(g + (uint32_t)ngrp, h_ahead);
+    const int v = (int)(uint32_t)e;
+    const uint32_t Q = (uint32_t)(e >> 32);
+    const bool fresh = h == c;                           // first reached by this hop: to be visited
+    // (list 1 may name a seed that a pick claimed before the seed's own visit took the entry over)
+    if (h == 1 && C.visit[v] != (vtag | Q)) continue;
+    // ---- hop c's picks of the node: drawn now, or held since its visit ----
+    int id = -1;
+    if (c == 0) {
+      if ((uint32_t)v < (uint32_t)RC.n_dst) {
+        // the seed's entry of the visit table: nobody waits for the result.  (A repeated seed is visited twice; the
+        // place phase reports it, and the step's results are discarded.)
+        if (sub == 0) claim_seed(C.visit, (uint32_t)v, vtag | Q);
+        id = visit_node(P, C, G, 0, v, Q);
+      } else {
+        // an id out of range (the place phase reports it): it holds no picks
+        for (int h = 0; h < L; ++h)
+          if (sub < C.f(h)) C.held[C.off[h] + Q * (uint32_t)C.f(h) + (uint32_t)sub] = -1;
+      }
+    } else if (fresh) {
+      id = visit_node(P, C, G, c, v, Q);
+    } else if (sub < fc) {
+      id = C.held[C.off[c] + Q * (uint32_t)fc + (uint32_t)sub];
+    }
+    if (!claims) continue;
+    // ---- every pick claims its node; the winners join list c + 1 ----
+    const uint32_t Qc = (uint32_t)C.V[c] + Q * (uint32_t)fc + (uint32_t)sub;
+    bool won = false;
+    if (id >= 0) won = claim_visit(C.visit, (uint32_t)id, vtag | Qc);
+    const uint64_t wm = __ballot(won);                   // both nodes of the wavefront: they share a segment
+    if (wm != 0ull) {
+      const uint32_t seg = (g >> 1) % CHAIN_SEGS;
+      const int leader = __ffsll((unsigned long long)wm) - 1;
+      uint32_t base = 0u;
+      if (lane_id() == leader) base = atomicAdd(&C.counts[((c + 1) * CHAIN_SEGS + seg) * CHAIN_COUNT_STRIDE], (uint32_t)__popcll(wm));
+      base = (uint32_t)__shfl((int)base, leader);
+      if (won) {
+        const uint32_t at = base + (uint32_t)__popcll(wm & ((1ull << lane_id()) - 1ull));
+        if (at < C.lcap[c + 1]) C.list[C.loff[c + 1] + seg * C.lcap[c + 1] + at] = ((uint64_t)Qc << 32) | (uint32_t)id;
+        // (beyond the capacity: cannot happen; the next chain phase reports the counter)
+      }
+    }
+  }
+}
+
+// place phase of hop h: tiles of pick slots in frontier order.  Slot i * f + j takes pick j of frontier node i from
+// the holding area (through the node's holding index in the visit table) and enters it into the dedupe table; rows
+// wg.y >= 1 of the slice handle the dst nodes.  From here on the hop looks like any other: mark, emit.
+template <class HP>
+__device__ __forceinline__ void place_phase(const HP& P, const Wg wg, LiveLds* live) {
+  if (wg.y >= 1) {
+    dst_node_rows(P, 0, wg.x);
+    return;
+  }
+  live_tiles_setup(P, live);
+  const TypeParam& TP = type_of(P, 0);
+  const uint32_t f = (uint32_t)P.f;
+  for (int j = wg.x; j < live->first[1]; j += P.gx) {
+    const LiveTile lt = live_tile(P, live, j);
+    const uint32_t nslots = lt.nslots;
+    const uint32_t g = lt.local0 + ITEMS_PER_THREAD * threadIdx.x;       // one relation: its slots start at 0
+    if (g >= nslots) continue;
+    uint32_t i = g / f, jj = g - i * f;
+    int id[ITEMS_PER_THREAD];
+    uint32_t Q = 0;
+    bool have = false;
+#pragma unroll
+    for (int q = 0; q < ITEMS_PER_THREAD; ++q) {
+      id[q] = -1;
+      if (g + q < nslots) {
+        if (!have || jj == 0u) {            // the first slot of the thread, or a new frontier node
+          have = true;
+          const int v = TP.frontier[i];
+          Q = 0xFFFFFFFFu;
+          if ((uint32_t)v < (uint32_t)TP.n_nodes) {
+            const uint64_t w = P.visit[v];
+            if ((uint32_t)(w >> 32) == ~P.visit_ver()) Q = (uint32_t)w;
+            else atomicOr(&P.state[ST_ERROR], ERR_TABLE_MISS);   // (cannot happen: every frontier node was visited)
+          }
+        }
+        if (Q != 0xFFFFFFFFu) id[q] = P.held[Q * f + jj];
+      }
+      if (++jj == f) { jj = 0u; ++i; }
+    }
+    *reinterpret_cast<int4*>(P.picks + g) = make_int4(id[0], id[1], id[2], id[3]);
+    const uint32_t key_off = TP.key_off;
+#pragma unroll
+    for (int q = 0; q < ITEMS_PER_THREAD; ++q)
+      if (id[q] >= 0) table_insert_min(P.ht, P.ver, key_off + (uint32_t)id[q], EDGE_BIT | (g + q), P.state);
   }
 }
 
@@ -949,7 +1194,7 @@ union TickLds {
 // spill code than the slots bring.
 // The workgroup `block` of the slice with arguments P.
 template <class HP>
-__device__ __forceinline__ void run_slice(const HP& P, int block) {
+__device__ __forceinline__ void run_slice(const HP& P, int block, const ChainArgs* C = nullptr) {
   // rows 0 .. gy-1 of the slice are gx workgroups wide, the gyd rows after them gxd (sample phase: the
   // rows of the node types need one thread per frontier node, not one 32-lane group)
   Wg wg;
@@ -960,12 +1205,20 @@ __device__ __forceinline__ void run_slice(const HP& P, int block) {
     while (wg.x >= P.gxd) { wg.x -= P.gxd; ++wg.y; }
   __shared__ TickLds lds;
   __shared__ LiveLds live;
+  __shared__ typename std::conditional<std::is_same<HP, HopParamsChain>::value, ChainLds, int>::type chain_lds;
+  (void)chain_lds;
   switch (P.phase) {
     case PH_SAMPLE: sample_phase(P, wg, lds.group); break;
     case PH_MARK:   mark_phase(P, wg, lds.scan, &live); break;
     case PH_SCAN:   scan_phase(P, lds.scan, &live); break;
     case PH_INSERT: insert_phase(P, wg, &live); break;
-    default:        emit_phase(P, wg, &lds.emit, &live); break;
+    case PH_EMIT:   emit_phase(P, wg, &lds.emit, &live); break;
+    default:
+      if constexpr (std::is_same<HP, HopParamsChain>::value) {     // (only this build holds the visit-once code)
+        if (P.phase == PH_PLACE) place_phase(P, wg, &live);
+        else if (P.phase == PH_CHAIN) chain_phase(P, *C, wg, lds.group, &chain_lds);
+      }
+      break;
   }
 }
 template <class TP>
@@ -973,7 +1226,9 @@ __device__ __forceinline__ void tick_body(const TP& M) {
   int z = 0;
 #pragma unroll
   for (int i = 0; i < TP::SLICES - 1; ++i) z += ((int)blockIdx.x >= M.end[i]) ? 1 : 0;
-  run_slice(M.s[z], (int)blockIdx.x - (z ? M.end[z - 1] : 0));
+  const ChainArgs* chain = nullptr;
+  if constexpr (TP::HAS_CHAIN) chain = &M.chain;
+  run_slice(M.s[z], (int)blockIdx.x - (z ? M.end[z - 1] : 0), chain);
 }
 // Two builds of the same kernel.  With its scalar registers capped at 96 the kernel takes 67-72 vector registers:
 // seven workgroups per CU.  The dense build is held to 64 (eight workgroups per CU) and pays for it with more scalar
@@ -1243,10 +1498,15 @@ int tick_capacity(int R, int T) {
 
 template <class HP, int D>
 static hipError_t launch_tick_t(const HopParams* P, int n, const RelConst* relc_host, const RelConst* relc_dev,
-                                hipStream_t st, LaunchTimer* timer, hipEvent_t done, bool dense) {
+                                const ChainArgs* chain, hipStream_t st, LaunchTimer* timer, hipEvent_t done, bool dense) {
   using TP = TickT<HP, D>;
   static_assert(sizeof(TP) <= 4000, "kernel arguments are limited to 4 KB");
   TP M;
+  if constexpr (TP::HAS_CHAIN) {
+    if (chain) M.chain = *chain; else memset(static_cast<void*>(&M.chain), 0, sizeof M.chain);
+  } else if (chain) {
+    return hipErrorInvalidValue;
+  }
   int total = 0;
   for (int i = 0; i < D; ++i) {
     const HopParams& src = P[i < n ? i : 0];        // unused slices repeat the first and own no workgroup
@@ -1319,33 +1579,41 @@ static hipError_t launch_tick_mono(const HopParams* P, int n, const RelConst* re
 }
 
 hipError_t launch_tick(const HopParams* P, int n, const RelConst* relc_host, const RelConst* relc_dev,
-                       const SlotConst* slots_dev, hipStream_t st, LaunchTimer* timer, hipEvent_t done, bool dense) {
+                       const SlotConst* slots_dev, bool chain_build, const ChainArgs* chain, hipStream_t st, LaunchTimer* timer,
+                       hipEvent_t done, bool dense) {
   if (n < 1 || n > tick_capacity(P[0].R, P[0].T)) return hipErrorInvalidValue;
   const int R = P[0].R, T = P[0].T;
+  if (chain_build) {
+    if (R != 1 || T != 1 || n > CHAIN_TICK_SLICES) return hipErrorInvalidValue;
+    if (n == 1) return launch_tick_t<HopParamsChain, 1>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    if (n <= 4) return launch_tick_t<HopParamsChain, 4>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    return launch_tick_t<HopParamsChain, CHAIN_TICK_SLICES>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+  }
+  if (chain) return hipErrorInvalidValue;
   if (R == 1 && T == 1 && n > 12) {
     if (!slots_dev) return hipErrorInvalidValue;
     return launch_tick_mono(P, n, relc_host, slots_dev, st, timer, done);
   }
   if (R == 1 && T == 1) {
-    if (n == 1) return launch_tick_t<HopParamsMono, 1>(P, n, relc_host, relc_dev, st, timer, done, dense);
-    if (n <= 4) return launch_tick_t<HopParamsMono, 4>(P, n, relc_host, relc_dev, st, timer, done, dense);
-    if (n <= 8) return launch_tick_t<HopParamsMono, 8>(P, n, relc_host, relc_dev, st, timer, done, dense);
-    return launch_tick_t<HopParamsMono, 12>(P, n, relc_host, relc_dev, st, timer, done, dense);
+    if (n == 1) return launch_tick_t<HopParamsMono, 1>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    if (n <= 4) return launch_tick_t<HopParamsMono, 4>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    if (n <= 8) return launch_tick_t<HopParamsMono, 8>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    return launch_tick_t<HopParamsMono, 12>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
   }
   if (R <= HopParamsSmall::MAX_R && T <= HopParamsSmall::MAX_T) {
-    if (n == 1) return launch_tick_t<HopParamsSmall, 1>(P, n, relc_host, relc_dev, st, timer, done, dense);
-    if (n <= 3) return launch_tick_t<HopParamsSmall, 3>(P, n, relc_host, relc_dev, st, timer, done, dense);
-    if (n <= 6) return launch_tick_t<HopParamsSmall, 6>(P, n, relc_host, relc_dev, st, timer, done, dense);
-    return launch_tick_t<HopParamsSmall, 9>(P, n, relc_host, relc_dev, st, timer, done, dense);
+    if (n == 1) return launch_tick_t<HopParamsSmall, 1>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    if (n <= 3) return launch_tick_t<HopParamsSmall, 3>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    if (n <= 6) return launch_tick_t<HopParamsSmall, 6>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    return launch_tick_t<HopParamsSmall, 9>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
   }
   if (R <= HopParamsMid::MAX_R && T <= HopParamsMid::MAX_T) {
-    if (n == 1) return launch_tick_t<HopParamsMid, 1>(P, n, relc_host, relc_dev, st, timer, done, dense);
-    if (n <= 3) return launch_tick_t<HopParamsMid, 3>(P, n, relc_host, relc_dev, st, timer, done, dense);
-    return launch_tick_t<HopParamsMid, 6>(P, n, relc_host, relc_dev, st, timer, done, dense);
+    if (n == 1) return launch_tick_t<HopParamsMid, 1>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    if (n <= 3) return launch_tick_t<HopParamsMid, 3>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    return launch_tick_t<HopParamsMid, 6>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
   }
-  if (n == 1) return launch_tick_t<HopParams, 1>(P, n, relc_host, relc_dev, st, timer, done, dense);
-  if (n == 2) return launch_tick_t<HopParams, 2>(P, n, relc_host, relc_dev, st, timer, done, dense);
-  return launch_tick_t<HopParams, 4>(P, n, relc_host, relc_dev, st, timer, done, dense);
+  if (n == 1) return launch_tick_t<HopParams, 1>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+  if (n == 2) return launch_tick_t<HopParams, 2>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+  return launch_tick_t<HopParams, 4>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
 }
 
 hipError_t launch_validate_graph(const void* indptr, int is64, int64_t n_dst, const int32_t* indices, int64_t nnz,

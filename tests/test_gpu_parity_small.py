@@ -465,3 +465,56 @@ def test_both_register_budgets_typed_graph(build, tuning):
     gt = synth.hetero_graph([1200, 2000, 60, 300], [(1, 2, 2600), (1, 0, 9000), (0, 0, 5000), (0, 3, 8000)], 2.2, seed=8)
     kw = dict(k=25, mode=OTF, num_layers=2, refresh_fraction=0.2, refresh_period=1, rng_seed=3)
     assert run_parity_pipelined(gt, kw, [25, 20], 100, steps=range(12)) > 0
+
+
+SHARED_CASES = [
+    # k, fraction, period, fanouts, batch, theta
+    (30, 0.10, 1, [15, 10, 5], 300, -1),
+    (17, 0.3, 1, [8, 5, 4], 150, -1),
+    (12, 0.25, 2, [3, 3], 500, -1),
+    (32, 1.0, 1, [8, 8, 8, 8], 40, -1),          # four hops, every slot redrawn at each visit
+    (24, 0.25, 1, [12, 12], 300, 30),           # degree split: nodes without a row draw from the adjacency per hop
+    (9, 0.5, 1, [9], 700, -1),                  # one hop
+    (20, 0.2, 1, [2, 3, 4, 5, 6], 30, -1),      # five hops: more than a visit-once step holds, runs hop by hop
+]
+
+
+@pytest.mark.parametrize("visit_once", [1, 2])
+@pytest.mark.parametrize("k,frac,period,fanouts,batch,theta", SHARED_CASES)
+def test_shared_table_steps_both_ways(k, frac, period, fanouts, batch, theta, visit_once, tuning):
+    # the shared table with a refresh per visit runs its steps as visit-once steps (each node visited by the first hop
+    # that reaches it, which draws all its remaining hops' picks) or hop by hop: the same blocks and tables either way
+    tuning(visit_once=visit_once)
+    g = graph_small()
+    kw = dict(k=k, mode=SHARED, num_layers=len(fanouts), refresh_fraction=frac, refresh_period=period, rng_seed=4242,
+              degree_threshold=theta)
+    assert run_parity(g, kw, fanouts, batch, steps=[0, 1, 2, 3, 5, 8]) > 0
+    assert run_parity_pipelined(g, kw, fanouts, batch, steps=range(25)) > 0
+
+
+def test_visit_once_steps_mixed_with_hop_by_hop_steps(tuning):
+    # steps of up to four hops run visit-once, a five-hop step between them hop by hop; batches of very different
+    # sizes (the holding area grows), an empty batch, repeated and out-of-range seeds
+    import torch
+    from paper_2406_17918_amd import gss
+    g = graph_small()
+    kw = dict(k=20, mode=SHARED, num_layers=5, refresh_fraction=0.2, refresh_period=1, rng_seed=9)
+    gs, os_ = gpu_sampler(g, kw), oracle_sampler(g, kw)
+    plan = [(0, 60, [5, 5, 5]), (1, 0, [5, 5]), (2, 7, [2, 3, 4, 5, 6]), (3, 900, [4, 4, 4, 4]), (4, 3, [20]),
+            (6, 2500, [6, 7]), (7, 33, [1, 2, 3, 4, 5]), (8, 64, [5, 5, 5])]
+    seeds = [synth.seeds_for_step(g.num_nodes[0], b, 3, st) for st, b, _ in plan]
+    dev = [torch.from_numpy(x).cuda() for x in seeds]
+    for i, (st, b, fan) in enumerate(plan[:4]):
+        assert_blocks_equal(gs.step(dev[i], fan, st), os_.step(seeds[i], fan, st), ctx=f"step {st}")
+    for i, (st, b, fan) in enumerate(plan[4:], 4):
+        gs.step_async(dev[i], fan, st)
+    for i, (st, b, fan) in enumerate(plan[4:], 4):
+        assert_blocks_equal(gs.step_wait(), os_.step(seeds[i], fan, st), ctx=f"pipelined step {st}")
+    assert np.array_equal(gs.cache(0).cpu().numpy(), os_.cache(0))
+    gs.close(); os_.close()
+    for bad in ([5, 6, 5], [5, g.num_nodes[0]], [-1, 2]):
+        s = gpu_sampler(g, kw)
+        with pytest.raises(gss.GssError) as e:
+            s.step(torch.tensor(bad, dtype=torch.int32, device="cuda"), [3, 3, 3], 0)
+        assert e.value.status == gss.GSS_ERR_INVALID_SEED
+        s.close()

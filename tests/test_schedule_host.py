@@ -12,7 +12,7 @@ import pytest
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SAMPLE, MARK, SCAN, EMIT, INSERT = 0, 1, 2, 3, 4
+SAMPLE, MARK, SCAN, EMIT, INSERT, PLACE, CHAIN = 0, 1, 2, 3, 4, 5, 6
 
 
 @pytest.fixture(scope="module")
@@ -22,16 +22,19 @@ def shim(tmp_path_factory):
                     os.path.join(ROOT, "paper_2406_17918_amd", "csrc"), os.path.join(HERE, "native", "schedule_shim.cpp"),
                     "-o", so], check=True)
     lib = C.CDLL(so)
-    lib.sched_items.argtypes = [C.c_int, C.c_uint, C.c_uint, C.POINTER(C.c_int8), C.POINTER(C.c_int8)]
-    lib.sched_plan.argtypes = [C.POINTER(C.c_int), C.POINTER(C.c_uint), C.POINTER(C.c_uint), C.POINTER(C.c_int), C.c_int,
-                               C.c_int, C.c_int, C.POINTER(C.c_int)]
+    lib.sched_items.argtypes = [C.c_int, C.c_uint, C.c_uint, C.c_int, C.POINTER(C.c_int8), C.POINTER(C.c_int8)]
+    pi = C.POINTER(C.c_int)
+    lib.sched_plan.argtypes = [pi, C.POINTER(C.c_uint), C.POINTER(C.c_uint), pi, pi, pi, C.c_int, C.c_int, C.c_int, pi, pi]
     return lib
 
 
-def items_of(layers, scan_hops, insert_hops=0):
+def items_of(layers, scan_hops, insert_hops=0, chain=False):
     out = []
     for h in range(layers):
-        out += [(h, SAMPLE)] + ([(h, INSERT)] if (insert_hops >> h) & 1 else []) + [(h, MARK)]
+        if chain:                 # a visit-once step: the place phase does the inserts itself
+            out += [(h, PLACE), (h, MARK)]
+        else:
+            out += [(h, SAMPLE)] + ([(h, INSERT)] if (insert_hops >> h) & 1 else []) + [(h, MARK)]
         out += ([(h, SCAN)] if (scan_hops >> h) & 1 else []) + [(h, EMIT)]
     return out
 
@@ -40,9 +43,10 @@ def test_phase_list_of_a_step(shim):
     for layers in range(1, 9):
         for scan_hops in (0, 1, 0b101, (1 << layers) - 1):
             for insert_hops in (0, 1 << (layers - 1), (1 << layers) - 1):
-                hop = (C.c_int8 * 48)(); phase = (C.c_int8 * 48)()
-                n = shim.sched_items(layers, scan_hops, insert_hops, hop, phase)
-                assert [(hop[i], phase[i]) for i in range(n)] == items_of(layers, scan_hops & ((1 << layers) - 1), insert_hops)
+                for chain in (0, 1):
+                    hop = (C.c_int8 * 48)(); phase = (C.c_int8 * 48)()
+                    n = shim.sched_items(layers, scan_hops, insert_hops, chain, hop, phase)
+                    assert [(hop[i], phase[i]) for i in range(n)] == items_of(layers, scan_hops & ((1 << layers) - 1), insert_hops, chain)
 
 
 class Sim:
@@ -50,40 +54,50 @@ class Sim:
 
     def __init__(self, shim, otf, shared):
         self.shim, self.otf, self.shared = shim, otf, shared
-        self.steps = []          # per step: dict(L, scan, next, issued_at={item index: tick})
+        self.steps = []          # per step: dict(L, scan, next, cnext, at={item index: tick}, cat={chain phase: tick})
         self.flight = []
         self.ticks = 0
 
-    def enqueue(self, layers, scan_hops=0, insert_hops=0):
+    def enqueue(self, layers, scan_hops=0, insert_hops=0, chain=False):
         # the driver lets the steps in flight finish issuing before a step of another depth joins (OTF, per-layer tables)
         if self.otf and not self.shared and self.flight and self.steps[self.flight[-1]]["L"] != layers:
             self.drain()
-        self.steps.append(dict(L=layers, scan=scan_hops, ins=insert_hops, next=0, at={},
-                               items=items_of(layers, scan_hops, insert_hops)))
+        self.steps.append(dict(L=layers, scan=scan_hops, ins=insert_hops, next=0, at={}, chain=chain, cnext=0, cat={},
+                               nchain=layers if chain else 0, items=items_of(layers, scan_hops, insert_hops, chain)))
         self.flight.append(len(self.steps) - 1)
         self.tick()
 
     def tick(self):
         n = len(self.flight)
-        L = (C.c_int * n)(*[self.steps[i]["L"] for i in self.flight])
-        sc = (C.c_uint * n)(*[self.steps[i]["scan"] for i in self.flight])
-        ins = (C.c_uint * n)(*[self.steps[i]["ins"] for i in self.flight])
-        nx = (C.c_int * n)(*[self.steps[i]["next"] for i in self.flight])
-        take = (C.c_int * max(n, 1))()
-        m = self.shim.sched_plan(L, sc, ins, nx, n, int(self.otf), int(self.shared), take)
-        assert 0 <= m <= n
-        chosen = [self.flight[take[j]] for j in range(m)]
-        assert chosen == sorted(set(chosen))                                  # one phase per step and tick
-        for i in chosen:
+        arr = lambda key, ty=C.c_int: (ty * max(n, 1))(*[int(self.steps[i][key]) for i in self.flight])
+        ts, ti = (C.c_int * (2 * n + 1))(), (C.c_int * (2 * n + 1))()
+        m = self.shim.sched_plan(arr("L"), arr("scan", C.c_uint), arr("ins", C.c_uint), arr("chain"), arr("next"),
+                                 arr("cnext"), n, int(self.otf), int(self.shared), ts, ti)
+        assert 0 <= m <= 2 * n
+        chosen = [(self.flight[ts[j]], ti[j]) for j in range(m)]
+        assert len(set(chosen)) == m and [c[0] for c in chosen] == sorted(c[0] for c in chosen)
+        for i in {c[0] for c in chosen}:                                      # at most one list phase and one chain phase per step
+            mine = [it for st_, it in chosen if st_ == i]
+            assert sum(it >= 0 for it in mine) <= 1 and sum(it < 0 for it in mine) <= 1
+        for i, it in chosen:
             st = self.steps[i]
-            assert st["next"] < len(st["items"])
-            st["at"][st["next"]] = self.ticks
-            st["next"] += 1
+            if it >= 0:
+                assert it == st["next"] < len(st["items"])
+                st["at"][it] = self.ticks
+                st["next"] += 1
+            else:
+                assert -1 - it == st["cnext"] < st["nchain"]
+                st["cat"][st["cnext"]] = self.ticks
+                st["cnext"] += 1
         self.ticks += 1
         return m
 
+    def is_open(self, i):
+        st = self.steps[i]
+        return st["next"] < len(st["items"]) or st["cnext"] < st["nchain"]
+
     def open(self):
-        return [i for i in self.flight if self.steps[i]["next"] < len(self.steps[i]["items"])]
+        return [i for i in self.flight if self.is_open(i)]
 
     def drain(self):
         while self.open():
@@ -91,10 +105,14 @@ class Sim:
 
     def wait_oldest(self):
         i = self.flight[0]
-        while self.steps[i]["next"] < len(self.steps[i]["items"]):
-            before = self.steps[i]["next"]
+        stalled = 0
+        while self.is_open(i):
+            before = self.steps[i]["next"] + self.steps[i]["cnext"]
             assert self.tick() >= 1
-            assert self.steps[i]["next"] == before + 1                        # the oldest step is always ready
+            # the oldest step makes progress - at once, except that a place phase may wait a few ticks for a younger
+            # step's chain to come round to its light hop
+            stalled = 0 if self.steps[i]["next"] + self.steps[i]["cnext"] > before else stalled + 1
+            assert stalled <= 8 and (stalled == 0 or self.steps[i]["chain"])
         self.flight.pop(0)
 
     def sample_tick(self, i, h):
@@ -156,3 +174,55 @@ def test_independent_steps_advance_together_and_a_full_pipeline_costs_one_tick_p
     while sim3.flight:
         sim3.wait_oldest()
     assert sim3.ticks == 20 * 7 + 2                                           # shared table: 7 ticks per step, 9 for the last
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_visit_once_steps(shim, seed):
+    # one table for all hops, refreshed per visit: chain phases (the only ones that touch the table) of consecutive
+    # steps never overlap and keep their order; a hop's place phase comes after its chain phase; old-style steps
+    # (sample phases touch the table) may be mixed in
+    rs = np.random.default_rng(seed)
+    sim = Sim(shim, otf=True, shared=True)
+    for step in range(80):
+        while len(sim.flight) >= 10 or (sim.flight and rs.random() < 0.2):
+            sim.wait_oldest()
+        layers = int(rs.choice([1, 2, 3, 3, 4]))
+        sim.enqueue(layers, scan_hops=int(rs.integers(0, 1 << layers)) if rs.random() < 0.3 else 0,
+                    chain=bool(seed == 0 or rs.random() < 0.7))
+    while sim.flight:
+        sim.wait_oldest()
+
+    def table_ticks(st):
+        return sorted(st["cat"].values()) if st["chain"] else [st["at"][st["items"].index((h, SAMPLE))] for h in range(st["L"])]
+    for i, st in enumerate(sim.steps):
+        ticks = [st["at"][j] for j in range(len(st["items"]))]
+        assert ticks == sorted(set(ticks))
+        if st["chain"]:
+            assert [st["cat"][c] for c in range(st["L"])] == sorted(set(st["cat"].values()))
+            for h in range(st["L"]):
+                assert st["cat"][h] < st["at"][st["items"].index((h, PLACE))]
+        if i:
+            assert max(table_ticks(sim.steps[i - 1])) < min(table_ticks(st))
+    # the place phases of the outer hops share a tick only with the chain phase of a hop 0, or with none
+    chain_hop_at = {}
+    for st in sim.steps:
+        for c, t in st["cat"].items():
+            assert t not in chain_hop_at                                       # one chain phase per tick
+            chain_hop_at[t] = c
+    for st in sim.steps:
+        if st["chain"]:
+            for h in range(1, st["L"]):
+                assert chain_hop_at.get(st["at"][st["items"].index((h, PLACE))], 0) == 0
+    if seed == 0:
+        # steady state of 3-hop steps: three ticks per step (the chain), the nine list phases trail behind
+        sim = Sim(shim, otf=True, shared=True)
+        for step in range(30):
+            if len(sim.flight) == 8:
+                sim.wait_oldest()
+            sim.enqueue(3, chain=True)
+        while sim.flight:
+            sim.wait_oldest()
+        st = sim.steps[10]
+        assert [st["cat"][c] for c in range(3)] == [30, 31, 32]
+        assert [st["at"][j] for j in range(9)] == [31, 32, 33, 36, 37, 38, 39, 40, 41]
+        assert sim.ticks == 30 * 3 + 7                                        # (the last step drains without waiting)
