@@ -70,7 +70,7 @@ typedef enum {
 typedef enum { GSS_MODE_FCR = 0, GSS_MODE_OTF = 1, GSS_MODE_SHARED_OTF = 2, GSS_MODE_FBL = 3,
                GSS_MODE_SHARED_FCR = 4, GSS_MODE_OTF_FETCH = 5, GSS_MODE_OTF_LAYER = 6 } gss_mode;
 
-#define GSS_MAX_K 32           /* one cache row fits half a wavefront                     */
+#define GSS_MAX_K 64           /* one cache row fits a wavefront (rows of up to 32 slots: half of one) */
 #define GSS_MAX_LAYERS 8
 #define GSS_MAX_NODE_TYPES 8
 #define GSS_MAX_RELATIONS 16

@@ -242,7 +242,7 @@ void release(gss_sampler* s, Buf& b) { dev_free(s, b.p); b.p = nullptr; b.bytes 
     if (e_ != hipSuccess) return fail(s, GSS_ERR_DEVICE, "%s: %s", #call, hipGetErrorString(e_)); \
   } while (0)
 
-int row_stride(int k) { return k <= 16 ? 16 : 32; }
+int row_stride(int k) { return k <= 16 ? 16 : k <= 32 ? 32 : 64; }
 
 int32_t n_new_of(double fraction, int k) {
   double x = fraction * (double)k + 1e-9;
@@ -397,9 +397,10 @@ void fill_slice(gss_sampler* s, Slot& sl, int it, HopParams& P) {
     // full tick - 16,384-seed steps +9 % with 8,192.  The shared-table refresh mode runs its sample phases nearly
     // alone, one step after the other: there 8,192 are 1.5 % faster)
     const int64_t cap = (s->otf && s->shared) ? 8192 : 2048;
-    P.gx = (int32_t)std::min<int64_t>(std::max<int64_t>((want + 8 * per - 1) / (8 * per), 1), cap);
-    P.gy = R;                                    // per relation: a 32-lane group per frontier node
-    P.gxd = (P.gx + 31) / 32; P.gyd = T;         // per node type: a thread per frontier node
+    const int64_t gpw = s->k > 32 ? 4 : 8;       // groups of a workgroup: 32 lanes per node, or 64 for rows of more than 32 slots
+    P.gx = (int32_t)std::min<int64_t>(std::max<int64_t>((want + gpw * per - 1) / (gpw * per), 1), cap);
+    P.gy = R;                                    // per relation: a group per frontier node
+    P.gxd = (int32_t)((P.gx * gpw + 255) / 256); P.gyd = T;   // per node type: a thread per frontier node
   } else if (P.phase == PH_SCAN) {
     P.gx = 1; P.gy = 1;
   } else {                                     // insert, place, mark, emit: tiles
@@ -687,7 +688,7 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   s->tick_cap = tick_capacity(s->R, s->T);
   // One table for all hops and a refresh per visit: the steps run as visit-once steps (chain phases) where the graph
   // has one relation; all its launches use the build of the step kernel that holds the chain's code and arguments.
-  s->visit_once = c->mode == GSS_MODE_SHARED_OTF && s->R == 1 && s->T == 1 && tn.visit_once != 2;
+  s->visit_once = c->mode == GSS_MODE_SHARED_OTF && s->R == 1 && s->T == 1 && s->k <= 32 && tn.visit_once != 2;
   if (s->visit_once) s->tick_cap = CHAIN_TICK_SLICES;
   if (tn.chain_workgroups) s->chain_wg_cap = tn.chain_workgroups;
   s->visit_once_forced = tn.visit_once == 1;
@@ -710,8 +711,8 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   // (one-relation graphs: the compact form carries 24).  Measured on the 1,024-seed workload: FBL and OTF fetch
   // -15 % per step; the epoch-refreshed modes gain nothing (their refresh kernel shares the chip with launches
   // twice as large) and keep one step per tick.
-  s->steps_per_tick = (!s->otf && !s->fcr && s->R == 1 && s->T == 1) ? 2 : 1;
-  if (tn.steps_per_tick) s->steps_per_tick = (!s->otf && tn.steps_per_tick == 2) ? 2 : 1;
+  s->steps_per_tick = (!s->otf && !s->fcr && s->R == 1 && s->T == 1 && s->k <= 32) ? 2 : 1;
+  if (tn.steps_per_tick) s->steps_per_tick = (!s->otf && s->k <= 32 && tn.steps_per_tick == 2) ? 2 : 1;
   // A step of L hops has up to 4 L phases, one per launch: with two more steps than that in flight the step a
   // caller waits for has left the queue before.  (Deeper rings only widen the memory the launches touch: every slot
   // has scratch and a dedupe table of its own - 4 L + 4 was 1 % slower on the 1,024-seed workloads, 4 L too shallow.)

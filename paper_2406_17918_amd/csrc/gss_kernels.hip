@@ -83,41 +83,67 @@ __device__ __forceinline__ int64_t load_indptr(const void* indptr, int is64, int
 }
 
 // ------------------------------------------------------------------------------------------
-// Half-wavefront groups.  A cache row has k <= 32 slots, so one node occupies 32 lanes and a
-// wavefront works on two nodes at once (every Philox block and every compare is shared by both).
+// Groups of W lanes.  A cache row of k <= 32 slots occupies half a wavefront (W = 32), and a
+// wavefront works on two nodes at once (every Philox block and every compare is shared by both);
+// rows of 33 .. 64 slots take the whole wavefront (W = 64).
 // Lanes of a group talk through a small LDS scratch: a lane writes its item, every lane then reads
 // item i at the same address (an LDS broadcast), which replaces per-iteration cross-lane moves.
 // LDS operations of one wavefront execute in order, so no barrier is needed inside a group; the
 // accesses are volatile to keep the compiler from reordering them.
 // ------------------------------------------------------------------------------------------
-constexpr int GRP = 32;
-struct GroupLds {
-  uint64_t prio[64];   // priorities by slot, or by adjacency position in the k < deg < 2k regime
-  uint64_t ab[64];     // lo: value fixed in the slot (or -1); hi: this round's candidate (or -2)
-  int32_t out[64];     // values compacted in position order
+template <int W>
+struct GroupLdsT {
+  uint64_t prio[2 * W];  // priorities by slot, or by adjacency position in the k < deg < 2k regime
+  uint64_t ab[2 * W];    // lo: value fixed in the slot (or -1); hi: this round's candidate (or -2)
+  int32_t out[2 * W];    // values compacted in position order
 };
-// LDS address space made explicit: volatile accesses through a generic pointer would be emitted as
-// flat memory instructions instead of ds_read / ds_write.
-typedef __attribute__((address_space(3))) volatile GroupLds* GroupLdsPtr;
-struct Grp {
+template <int W> using MaskT = typename std::conditional<W == 64, uint64_t, uint32_t>::type;   // one bit per lane of a group
+__device__ __forceinline__ int mask_popc(uint32_t m) { return __popc(m); }
+__device__ __forceinline__ int mask_popc(uint64_t m) { return __popcll((unsigned long long)m); }
+__device__ __forceinline__ int mask_ffs(uint32_t m) { return __ffs((int)m); }
+__device__ __forceinline__ int mask_ffs(uint64_t m) { return __ffsll((unsigned long long)m); }
+template <int W>
+struct GrpT {
+  static constexpr int WIDTH = W;
+  static constexpr int LOG2_WIDTH = W == 64 ? 6 : 5;
+  using Mask = MaskT<W>;
+  // LDS address space made explicit: volatile accesses through a generic pointer would be emitted as
+  // flat memory instructions instead of ds_read / ds_write.
+  typedef __attribute__((address_space(3))) volatile GroupLdsT<W>* LdsPtr;
   int sub;                 // lane within the group
-  int half;                // group within the wavefront
-  GroupLdsPtr L;
+  int half;                // group within the wavefront (W = 32)
+  LdsPtr L;
+  __device__ __forceinline__ void init(GroupLdsT<W>* lds) {        // `lds`: one scratch per group of the workgroup
+    sub = (int)(threadIdx.x & (unsigned)(W - 1));
+    half = W == 32 ? (int)((threadIdx.x >> 5) & 1u) : 0;
+    L = (LdsPtr)&lds[threadIdx.x / (unsigned)W];
+  }
+  __device__ __forceinline__ Mask below() const { return ((Mask)1 << sub) - (Mask)1; }          // the lanes before this one
+  __device__ __forceinline__ bool in(Mask m) const { return ((m >> sub) & (Mask)1) != 0; }       // is this lane's bit set
+  __device__ __forceinline__ static Mask first(int n) { return n >= W ? ~(Mask)0 : (((Mask)1 << n) - (Mask)1); }
 };
-__device__ __forceinline__ uint32_t grp_ballot(const Grp& G, bool pred) {
+constexpr int GRP = 32;
+using GroupLds = GroupLdsT<32>;
+using Grp = GrpT<32>;
+using GroupLdsPtr = Grp::LdsPtr;
+template <int W>
+__device__ __forceinline__ MaskT<W> grp_ballot(const GrpT<W>& G, bool pred) {
   const uint64_t b = __ballot(pred);
-  return G.half ? (uint32_t)(b >> 32) : (uint32_t)b;
+  if constexpr (W == 64) return b;
+  else return G.half ? (uint32_t)(b >> 32) : (uint32_t)b;
 }
 __device__ __forceinline__ uint32_t below_mask(int sub) { return (1u << sub) - 1u; }
 
 // number of the n priorities in LDS smaller than p (all priorities are distinct)
-__device__ __forceinline__ int grp_rank(const Grp& G, int n, uint64_t p) {
+template <int W>
+__device__ __forceinline__ int grp_rank(const GrpT<W>& G, int n, uint64_t p) {
   int r = 0;
 #pragma unroll 4
   for (int i = 0; i < n; ++i) r += (G.L->prio[i] < p) ? 1 : 0;
   return r;
 }
-__device__ __forceinline__ void grp_rank2(const Grp& G, int n, uint64_t p0, uint64_t p1, int& r0, int& r1) {
+template <int W>
+__device__ __forceinline__ void grp_rank2(const GrpT<W>& G, int n, uint64_t p0, uint64_t p1, int& r0, int& r1) {
   r0 = 0; r1 = 0;
 #pragma unroll 4
   for (int i = 0; i < n; ++i) {
@@ -134,16 +160,18 @@ __device__ __forceinline__ void grp_rank2(const Grp& G, int n, uint64_t p0, uint
 // FEW: few slots are pending (a partial refresh): instead of every lane scanning all k slots, the
 // group walks over the pending slots, and every lane compares its own id with that slot's proposal.
 // From eight pending slots down, several rounds are drawn at once (below).
-template <bool FEW>
-__device__ __forceinline__ int grp_rejection_fill(const Grp& G, uint32_t pend, uint32_t fixed, int val, int k,
+template <bool FEW, int W>
+__device__ __forceinline__ int grp_rejection_fill(const GrpT<W>& G, MaskT<W> pend, MaskT<W> fixed, int val, int k,
                                                   const int32_t* __restrict__ adj, uint32_t deg,
                                                   const DrawKey& K, uint32_t purpose, int32_t* state) {
+  using Mask = MaskT<W>;
+  constexpr int GRP = W;
   for (uint32_t a = 0; pend != 0; ++a) {
     if (a >= 65536u) {   // acceptance probability is > 1/2 per draw: unreachable for a simple graph
       if (G.sub == 0) atomicOr(&state[ST_ERROR], ERR_REJECT_OVERFLOW);
       break;
     }
-    const int np = __popc(pend);
+    const int np = mask_popc(pend);
     if (!FEW && np <= 8 && a + (uint32_t)GRP <= 65536u) {
       // Few slots pending: a round would run the whole Philox block and a trip to the adjacency for a handful of
       // lanes.  Instead the 32 lanes compute the proposals of A = 16 / 8 / 4 consecutive rounds at once (lane ->
@@ -151,25 +179,25 @@ __device__ __forceinline__ int grp_rejection_fill(const Grp& G, uint32_t pend, u
       // resolved in order from LDS: same outcome, one block and one trip for all of them.
       const int lg = np <= 2 ? 1 : (np <= 4 ? 2 : 3);
       const int A = GRP >> lg;
-      const int q = G.sub >> (5 - lg), t = G.sub & (A - 1);
-      uint32_t m = pend;
-      for (int i = 0; i < q; ++i) m &= m - 1u;                       // drop the q lowest pending slots
-      const int jq = (q < np) ? __ffs((int)m) - 1 : -1;              // slot of pending index q
+      const int q = G.sub >> (GrpT<W>::LOG2_WIDTH - lg), t = G.sub & (A - 1);
+      Mask m = pend;
+      for (int i = 0; i < q; ++i) m &= m - (Mask)1;                  // drop the q lowest pending slots
+      const int jq = (q < np) ? mask_ffs(m) - 1 : -1;                // slot of pending index q
       int c = -3;
       if (jq >= 0) c = adj[below(lo64(draw_block(K, purpose, (uint32_t)jq, a + (uint32_t)t)), deg)];
       G.L->out[G.sub] = c;                                           // proposal of (q, t) at q * A + t
-      const bool mine0 = (pend >> G.sub) & 1u;
-      const int my_q = __popc(pend & below_mask(G.sub));             // pending index of the lane's own slot
+      const bool mine0 = G.in(pend);
+      const int my_q = mask_popc(pend & G.below());                  // pending index of the lane's own slot
       uint32_t pm = (1u << np) - 1u;                                 // pending, by pending index
       for (int tt = 0; tt < A && pm != 0u; ++tt) {
-        const bool have = (fixed >> G.sub) & 1u;
+        const bool have = G.in(fixed);
         uint32_t acc = 0u;
         for (uint32_t w = pm; w != 0u; w &= w - 1u) {               // (w is the same in all lanes of the group)
           const int qq = __ffs((int)w) - 1;
           const int cj = G.L->out[qq * A + tt];
           // lane l < np stands for the pending slot of index l: a lower pending slot with the same proposal
           const bool lower = G.sub < qq && ((pm >> G.sub) & 1u) && G.L->out[G.sub * A + tt] == cj;
-          if (grp_ballot(G, (have && val == cj) || lower) == 0u) acc |= 1u << qq;
+          if (grp_ballot(G, (have && val == cj) || lower) == (Mask)0) acc |= 1u << qq;
         }
         const bool got = mine0 && ((acc >> my_q) & 1u);
         if (got) val = G.L->out[my_q * A + tt];
@@ -180,23 +208,23 @@ __device__ __forceinline__ int grp_rejection_fill(const Grp& G, uint32_t pend, u
       a += (uint32_t)A - 1u;
       continue;
     }
-    const bool mine = (pend >> G.sub) & 1u;
+    const bool mine = G.in(pend);
     int cand = -3;
     if (mine) cand = adj[below(lo64(draw_block(K, purpose, (uint32_t)G.sub, a)), deg)];
     bool reject = false;
     if (FEW) {
-      const bool have = (fixed >> G.sub) & 1u;
+      const bool have = G.in(fixed);
       if (mine) G.L->out[G.sub] = cand;
-      for (uint32_t m = pend; m != 0; m &= m - 1u) {       // m is the same in all lanes of the group
-        const int j = __ffs((int)m) - 1;
+      for (Mask m = pend; m != 0; m &= m - (Mask)1) {      // m is the same in all lanes of the group
+        const int j = mask_ffs(m) - 1;
         const int cj = G.L->out[j];
         const bool hit = (have && val == cj) || (mine && G.sub < j && cand == cj);
-        const bool taken = grp_ballot(G, hit) != 0u;
+        const bool taken = grp_ballot(G, hit) != (Mask)0;
         if (G.sub == j) reject = taken;
       }
     } else {
       if (G.sub < k) {
-        const int fx = ((fixed >> G.sub) & 1u) ? val : -1;
+        const int fx = G.in(fixed) ? val : -1;
         G.L->ab[G.sub] = (uint64_t)(uint32_t)fx | ((uint64_t)(uint32_t)(mine ? cand : -2) << 32);
       }
 #pragma unroll 4
@@ -207,18 +235,19 @@ __device__ __forceinline__ int grp_rejection_fill(const Grp& G, uint32_t pend, u
     }
     const bool acc = mine && !reject;
     if (acc) val = cand;
-    const uint32_t accm = grp_ballot(G, acc);
+    const Mask accm = grp_ballot(G, acc);
     pend &= ~accm;
     fixed |= accm;
   }
   return val;
 }
 
-// k < deg < 2k <= 64: the group owns adjacency positions sub and sub + 32.  The `want` eligible
+// k < deg < 2k <= 2 W: the group owns adjacency positions sub and sub + W.  The `want` eligible
 // positions of smallest priority are written to L->out[0..want) in ascending position order.
-__device__ __forceinline__ void grp_select_positions(const Grp& G, int d, int want, bool elig0, bool elig1,
+template <int W>
+__device__ __forceinline__ void grp_select_positions(const GrpT<W>& G, int d, int want, bool elig0, bool elig1,
                                                      int a0, int a1, const DrawKey& K, uint32_t purpose) {
-  const int p0 = G.sub, p1 = G.sub + GRP;
+  const int p0 = G.sub, p1 = G.sub + W;
   uint64_t q0 = PRIO_NONE, q1 = PRIO_NONE;
   if (elig0) q0 = priority(lo64(draw_block(K, purpose, (uint32_t)p0, 0)), (uint32_t)p0);
   if (elig1) q1 = priority(lo64(draw_block(K, purpose, (uint32_t)p1, 0)), (uint32_t)p1);
@@ -227,14 +256,16 @@ __device__ __forceinline__ void grp_select_positions(const Grp& G, int d, int wa
   int r0, r1;
   grp_rank2(G, d, q0, q1, r0, r1);
   const bool s0 = elig0 && r0 < want, s1 = elig1 && r1 < want;
-  const uint32_t m0 = grp_ballot(G, s0), m1 = grp_ballot(G, s1);
-  if (s0) G.L->out[__popc(m0 & below_mask(G.sub))] = a0;
-  if (s1) G.L->out[__popc(m0) + __popc(m1 & below_mask(G.sub))] = a1;
+  const MaskT<W> m0 = grp_ballot(G, s0), m1 = grp_ballot(G, s1);
+  if (s0) G.L->out[mask_popc(m0 & G.below())] = a0;
+  if (s1) G.L->out[mask_popc(m0) + mask_popc(m1 & G.below())] = a1;
 }
 
 // FILL_FULL for one row: returns the value of slot `sub` (-1 beyond the row).
-__device__ __forceinline__ int grp_fill_full_row(const Grp& G, const int32_t* __restrict__ adj, uint32_t deg, int k,
+template <int W>
+__device__ __forceinline__ int grp_fill_full_row(const GrpT<W>& G, const int32_t* __restrict__ adj, uint32_t deg, int k,
                                                  const DrawKey& K, uint32_t purpose, int32_t* state) {
+  constexpr int GRP = W;
   if (deg <= (uint32_t)k) return ((uint32_t)G.sub < deg) ? adj[G.sub] : -1;
   if (deg < 2u * (uint32_t)k) {
     const int d = (int)deg;
@@ -243,30 +274,31 @@ __device__ __forceinline__ int grp_fill_full_row(const Grp& G, const int32_t* __
     grp_select_positions(G, d, k, e0, e1, a0, a1, K, purpose);
     return (G.sub < k) ? G.L->out[G.sub] : -1;
   }
-  const uint32_t slots = (k >= 32) ? 0xFFFFFFFFu : ((1u << k) - 1u);
-  const int v = grp_rejection_fill<false>(G, slots, 0u, -1, k, adj, deg, K, purpose, state);
+  const int v = grp_rejection_fill<false>(G, GrpT<W>::first(k), (MaskT<W>)0, -1, k, adj, deg, K, purpose, state);
   return (G.sub < k) ? v : -1;
 }
 
 // REFRESH_PART for one full row of a node with deg > k (Alg. 2 RefreshCache): the n_new slots of smallest
 // EVICT priority (`sb`: the slot's EVICT/PICK block) are redrawn from adj(v) \ retained.  `val` is the slot's
 // current id; returns its new one and the mask of redrawn slots.
-__device__ __forceinline__ int grp_refresh_part(const Grp& G, int val, int k, int n_new, const Block4& sb,
+template <int W>
+__device__ __forceinline__ int grp_refresh_part(const GrpT<W>& G, int val, int k, int n_new, const Block4& sb,
                                                 const int32_t* __restrict__ adj, uint32_t deg, const DrawKey& K,
-                                                int32_t* state, uint32_t& evict) {
+                                                int32_t* state, MaskT<W>& evict) {
+  constexpr int GRP = W;
   const int sub = G.sub;
-  const uint32_t slots = (k >= 32) ? 0xFFFFFFFFu : ((1u << k) - 1u);
+  const MaskT<W> slots = GrpT<W>::first(k);
   const uint64_t e = (sub < k) ? priority(lo64(sb), (uint32_t)sub) : PRIO_NONE;
   G.L->prio[sub] = e;
   const int er = grp_rank(G, k, e);
   evict = grp_ballot(G, sub < k && er < n_new);
-  const uint32_t retained = slots & ~evict;
+  const MaskT<W> retained = slots & ~evict;
   if (deg < 2u * (uint32_t)k) {
     // priority regime: a position is eligible unless its id sits in a retained slot
     const int d = (int)deg;
     bool e0 = sub < d, e1 = sub + GRP < d;
     const int a0 = e0 ? adj[sub] : -1, a1 = e1 ? adj[sub + GRP] : -1;
-    if (sub < k) G.L->ab[sub] = (uint64_t)(uint32_t)(((retained >> sub) & 1u) ? val : -1);
+    if (sub < k) G.L->ab[sub] = (uint64_t)(uint32_t)(G.in(retained) ? val : -1);
 #pragma unroll 4
     for (int j = 0; j < k; ++j) {
       const int rv = (int)(uint32_t)G.L->ab[j];
@@ -274,7 +306,7 @@ __device__ __forceinline__ int grp_refresh_part(const Grp& G, int val, int k, in
       e1 &= (rv != a1);
     }
     grp_select_positions(G, d, n_new, e0, e1, a0, a1, K, P_FILL_PART);
-    if ((evict >> sub) & 1u) val = G.L->out[__popc(evict & below_mask(sub))];
+    if (G.in(evict)) val = G.L->out[mask_popc(evict & G.below())];
   } else {
     val = grp_rejection_fill<true>(G, evict, retained, val, k, adj, deg, K, P_FILL_PART, state);
   }
@@ -290,19 +322,18 @@ __device__ __forceinline__ int grp_refresh_part(const Grp& G, int val, int k, in
 //      32-lane groups, so both halves of every wavefront run the Philox / rejection code together.
 // ------------------------------------------------------------------------------------------
 constexpr int FILL_CHUNK = 64;    // rows per chunk: small enough that a few thousand workgroups share the rejection work
+template <int W>
 __global__ __launch_bounds__(256) void fill_full_kernel(FillParams P) {
-  __shared__ GroupLds lds[8];
+  __shared__ GroupLdsT<W> lds[256 / W];
   __shared__ long long row_base[FILL_CHUNK];
   __shared__ int row_deg[FILL_CHUNK];
   __shared__ int row_at[FILL_CHUNK];          // table row of the node, -1: the node keeps no row (degree split)
   __shared__ int heavy_rows[FILL_CHUNK];
   __shared__ int wave_heavy[4];
-  Grp G;
-  G.sub = (int)(threadIdx.x & 31u);
-  G.half = (int)((threadIdx.x >> 5) & 1u);
-  G.L = (GroupLdsPtr)&lds[threadIdx.x >> 5];
+  GrpT<W> G;
+  G.init(lds);
   const int tid = (int)threadIdx.x, lane = lane_id(), wave = tid >> 6;
-  const int sshift = (P.S == 32) ? 5 : 4;
+  const int sshift = (P.S == 64) ? 6 : (P.S == 32) ? 5 : 4;
   const int64_t nchunks = (P.n_dst + FILL_CHUNK - 1) / FILL_CHUNK;
   for (int64_t chunk = blockIdx.x; chunk < nchunks; chunk += gridDim.x) {
     const int64_t v0 = chunk * FILL_CHUNK;
@@ -335,9 +366,9 @@ __global__ __launch_bounds__(256) void fill_full_kernel(FillParams P) {
       for (int t = 0; t < P.ntab; ++t) P.table[t][at] = val;
     }
     __syncthreads();
-    // ---- C: heavy rows, one 32-lane group per (row, table) ----
+    // ---- C: heavy rows, one W-lane group per (row, table) ----
     const int items = nheavy * P.ntab;
-    for (int it = tid >> 5; it < items; it += 8) {
+    for (int it = tid / W; it < items; it += 256 / W) {
       const int row = heavy_rows[it / P.ntab], t = it % P.ntab;
       const int64_t v = v0 + row;
       DrawKey K{P.seed_lo, P.seed_hi, (uint32_t)v, P.stepword, (P.layer_word[t] << 8) | (P.relation << 16)};
@@ -347,7 +378,7 @@ __global__ __launch_bounds__(256) void fill_full_kernel(FillParams P) {
         val = (G.sub < P.k) ? P.src_table[t][((int64_t)row_at[row] << sshift) + G.sub] : -1;
         Block4 sb{0u, 0u, 0u, 0u};
         if (G.sub < P.k) sb = draw_block(K, P_EVICT, (uint32_t)G.sub, 0);
-        uint32_t evict;
+        MaskT<W> evict;
         val = grp_refresh_part(G, val, P.k, P.n_new, sb, P.indices + row_base[row], (uint32_t)row_deg[row], K, P.state, evict);
       } else {
         val = grp_fill_full_row(G, P.indices + row_base[row], (uint32_t)row_deg[row], P.k, K, P_FILL_FULL, P.state);
@@ -361,15 +392,15 @@ __global__ __launch_bounds__(256) void fill_full_kernel(FillParams P) {
 // fill_heavy_kernel: the same rows for a table set that has been filled before.  Rows of nodes with at most k
 // neighbors hold the whole adjacency and never change, so a later refresh only recomputes the rows of the nodes
 // with more (a list made once at set-up): one 32-lane group per (row, table), no chunk staging, no barriers.
+template <int W>
 __global__ __launch_bounds__(256) void fill_heavy_kernel(FillParams P, const int32_t* __restrict__ heavy, int64_t nheavy) {
-  __shared__ GroupLds lds[8];
-  Grp G;
-  G.sub = (int)(threadIdx.x & 31u);
-  G.half = (int)((threadIdx.x >> 5) & 1u);
-  G.L = (GroupLdsPtr)&lds[threadIdx.x >> 5];
-  const int sshift = (P.S == 32) ? 5 : 4;
+  __shared__ GroupLdsT<W> lds[256 / W];
+  GrpT<W> G;
+  G.init(lds);
+  constexpr int GROUPS = 256 / W;
+  const int sshift = (P.S == 64) ? 6 : (P.S == 32) ? 5 : 4;
   const int64_t items = nheavy * P.ntab;
-  for (int64_t it = (int64_t)blockIdx.x * 8 + (int64_t)(threadIdx.x >> 5); it < items; it += (int64_t)gridDim.x * 8) {
+  for (int64_t it = (int64_t)blockIdx.x * GROUPS + (int64_t)(threadIdx.x / W); it < items; it += (int64_t)gridDim.x * GROUPS) {
     const int64_t v = heavy[it / P.ntab];
     const int t = (int)(it % P.ntab);
     const int64_t b = load_indptr(P.indptr, P.is64, v);
@@ -381,7 +412,7 @@ __global__ __launch_bounds__(256) void fill_heavy_kernel(FillParams P, const int
       val = (G.sub < P.k) ? P.src_table[t][at + G.sub] : -1;
       Block4 sb{0u, 0u, 0u, 0u};
       if (G.sub < P.k) sb = draw_block(K, P_EVICT, (uint32_t)G.sub, 0);
-      uint32_t evict;
+      MaskT<W> evict;
       val = grp_refresh_part(G, val, P.k, P.n_new, sb, P.indices + b, deg, K, P.state, evict);
     } else {
       val = grp_fill_full_row(G, P.indices + b, deg, P.k, K, P_FILL_FULL, P.state);
@@ -533,25 +564,25 @@ __device__ __forceinline__ void dst_node_rows(const HP& P, int t, int x) {
   }
 }
 
-template <class HP>
-__device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLds* lds) {
+template <class HP, int W>
+__device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLdsT<W>* lds) {
   if (wg.y >= P.R) {
     dst_node_rows(P, wg.y - P.R, wg.x);
     return;
   }
-  Grp G;
-  G.sub = (int)(threadIdx.x & 31u);
-  G.half = (int)((threadIdx.x >> 5) & 1u);
-  G.L = (GroupLdsPtr)&lds[threadIdx.x >> 5];
+  using Mask = MaskT<W>;
+  constexpr int GRP = W;
+  GrpT<W> G;
+  G.init(lds);
   const int r = wg.y;
   const RelParam& RP = rel_of(P, r);
   const RelConst& RC = P.rc(r);
-  const int grp = wg.x * (int)(blockDim.x >> 5) + (int)(threadIdx.x >> 5);
+  const int grp = wg.x * (int)(blockDim.x / W) + (int)(threadIdx.x / W);
   // the first node id is loaded before the frontier size is known (both loads travel together);
   // `frontier_cap` is the allocated length of the frontier array
   const int v_first = (grp < type_of(P, RP.dst_type).frontier_cap) ? type_of(P, RP.dst_type).frontier[grp] : 0;
   const int F = frontier_count(P, RP.dst_type);
-  const int ngrp = P.gx * (int)(blockDim.x >> 5);
+  const int ngrp = P.gx * (int)(blockDim.x / W);
   const int k = P.k, f = P.f, sub = G.sub;
   const int32_t* __restrict__ frontier = type_of(P, RP.dst_type).frontier;
   const uint32_t src_key_off = type_of(P, RP.src_type).key_off;
@@ -602,7 +633,7 @@ __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLds*
       }
       if (P.mode == GSS_MODE_SHARED_OTF) stamp = RC.stamp[at];
     }
-    const int len = __popc(grp_ballot(G, val >= 0));
+    const int len = mask_popc(grp_ballot(G, val >= 0));
 
     // ---- does this visit refresh the row? (only full rows can belong to a node with deg > k) ----
     bool refresh = false;
@@ -624,9 +655,9 @@ __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLds*
     if ((refresh || len > fdraw) && sub < k) sb = draw_block(K, P_EVICT, (uint32_t)sub, 0);
 
     if (refresh) {
-      uint32_t evict;
+      Mask evict;
       val = grp_refresh_part(G, val, k, P.n_new, sb, RC.indices + b, deg, K, P.state, evict);
-      if ((evict >> sub) & 1u) row[sub] = val;
+      if (G.in(evict)) row[sub] = val;
     }
 
     // ---- draw the fanout from the row ----
@@ -644,18 +675,18 @@ __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLds*
       // the cached picks move to lanes 0 .. fdraw-1 (ascending slot order); lanes fdraw .. f-1 draw fresh
       // neighbors from adj(v) \ {cached picks} by the redraw procedure of the partial refresh, on this
       // f-wide list instead of the row
-      const uint32_t selm0 = grp_ballot(G, sel);
-      if (sel) G.L->out[__popc(selm0 & below_mask(sub))] = val;
+      const Mask selm0 = grp_ballot(G, sel);
+      if (sel) G.L->out[mask_popc(selm0 & G.below())] = val;
       int cv = (sub < fdraw) ? G.L->out[sub] : -1;
-      const uint32_t kept = (1u << fdraw) - 1u;                       // fdraw < f <= 32
-      const uint32_t redraw = ((f >= 32) ? 0xFFFFFFFFu : ((1u << f) - 1u)) & ~kept;
+      const Mask kept = GrpT<W>::first(fdraw);                        // fdraw < f <= W
+      const Mask redraw = GrpT<W>::first(f) & ~kept;
       const int32_t* adj = RC.indices + b;
       const uint32_t deg = (uint32_t)d64;
       if (deg < 2u * (uint32_t)f) {
         const int d = (int)deg;
         bool e0 = sub < d, e1 = sub + GRP < d;
         const int a0 = e0 ? adj[sub] : -1, a1 = e1 ? adj[sub + GRP] : -1;
-        if (sub < f) G.L->ab[sub] = (uint64_t)(uint32_t)(((kept >> sub) & 1u) ? cv : -1);
+        if (sub < f) G.L->ab[sub] = (uint64_t)(uint32_t)(G.in(kept) ? cv : -1);
 #pragma unroll 4
         for (int j = 0; j < f; ++j) {
           const int rv = (int)(uint32_t)G.L->ab[j];
@@ -663,7 +694,7 @@ __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLds*
           e1 &= (rv != a1);
         }
         grp_select_positions(G, d, P.n_new, e0, e1, a0, a1, K, P_FETCH);
-        if ((redraw >> sub) & 1u) cv = G.L->out[__popc(redraw & below_mask(sub))];
+        if (G.in(redraw)) cv = G.L->out[mask_popc(redraw & G.below())];
       } else {
         cv = grp_rejection_fill<true>(G, redraw, kept, cv, f, adj, deg, K, P_FETCH, P.state);
       }
@@ -671,10 +702,10 @@ __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLds*
       sel = sub < f;
     }
     }
-    const uint32_t selm = grp_ballot(G, sel);
-    const int cnt = __popc(selm);
+    const Mask selm = grp_ballot(G, sel);
+    const int cnt = mask_popc(selm);
     if (sel) {
-      const uint32_t g = g0 + (uint32_t)__popc(selm & below_mask(sub));
+      const uint32_t g = g0 + (uint32_t)mask_popc(selm & G.below());
       P.picks[g] = val;
       if (!P.insert_split) table_insert_min(P.ht, P.ver, src_key_off + (uint32_t)val, EDGE_BIT | g, P.state);
     }
@@ -778,9 +809,7 @@ struct ChainLds { uint32_t start[CHAIN_MAX_HOPS * CHAIN_SEGS + 2]; };
 template <class HP>
 __device__ __forceinline__ void chain_phase(const HP& P, const ChainArgs& C, const Wg wg, GroupLds* lds, ChainLds* CL) {
   Grp G;
-  G.sub = (int)(threadIdx.x & 31u);
-  G.half = (int)((threadIdx.x >> 5) & 1u);
-  G.L = (GroupLdsPtr)&lds[threadIdx.x >> 5];
+  G.init(lds);
   const int c = P.hop, sub = G.sub, L = C.L;
   const int grp = wg.x * (int)(blockDim.x >> 5) + (int)(threadIdx.x >> 5);
   const int ngrp = P.gx * (int)(blockDim.x >> 5);
@@ -1183,8 +1212,9 @@ __device__ __forceinline__ void emit_phase(const HP& P, const Wg wg, EmitLds* L,
 // step_tick_kernel: a one-dimensional grid holds the workgroups of all slices back to back (slice i
 // owns [end[i-1], end[i]), x-major within its gx * gy rectangle), so no workgroup is launched in vain.
 // ------------------------------------------------------------------------------------------
+template <int W>
 union TickLds {
-  GroupLds group[8];
+  GroupLdsT<W> group[256 / W];
   int scan[32];
   EmitLds emit;
 };
@@ -1193,7 +1223,7 @@ union TickLds {
 // 96 it is 7 (223 per XCD); the spills go to lanes of a vector register.  Capping further for 8 costs more in
 // spill code than the slots bring.
 // The workgroup `block` of the slice with arguments P.
-template <class HP>
+template <int W, class HP>
 __device__ __forceinline__ void run_slice(const HP& P, int block, const ChainArgs* C = nullptr) {
   // rows 0 .. gy-1 of the slice are gx workgroups wide, the gyd rows after them gxd (sample phase: the
   // rows of the node types need one thread per frontier node, not one 32-lane group)
@@ -1203,9 +1233,9 @@ __device__ __forceinline__ void run_slice(const HP& P, int block, const ChainArg
   while (wg.y < P.gy && wg.x >= P.gx) { wg.x -= P.gx; ++wg.y; }
   if (wg.y == P.gy && P.gxd > 0)
     while (wg.x >= P.gxd) { wg.x -= P.gxd; ++wg.y; }
-  __shared__ TickLds lds;
+  __shared__ TickLds<W> lds;
   __shared__ LiveLds live;
-  __shared__ typename std::conditional<std::is_same<HP, HopParamsChain>::value, ChainLds, int>::type chain_lds;
+  __shared__ typename std::conditional<std::is_same<HP, HopParamsChain>::value && W == 32, ChainLds, int>::type chain_lds;
   (void)chain_lds;
   switch (P.phase) {
     case PH_SAMPLE: sample_phase(P, wg, lds.group); break;
@@ -1214,32 +1244,32 @@ __device__ __forceinline__ void run_slice(const HP& P, int block, const ChainArg
     case PH_INSERT: insert_phase(P, wg, &live); break;
     case PH_EMIT:   emit_phase(P, wg, &lds.emit, &live); break;
     default:
-      if constexpr (std::is_same<HP, HopParamsChain>::value) {     // (only this build holds the visit-once code)
+      if constexpr (std::is_same<HP, HopParamsChain>::value && W == 32) {     // (only this build holds the visit-once code)
         if (P.phase == PH_PLACE) place_phase(P, wg, &live);
         else if (P.phase == PH_CHAIN) chain_phase(P, *C, wg, lds.group, &chain_lds);
       }
       break;
   }
 }
-template <class TP>
+template <class TP, int W>
 __device__ __forceinline__ void tick_body(const TP& M) {
   int z = 0;
 #pragma unroll
   for (int i = 0; i < TP::SLICES - 1; ++i) z += ((int)blockIdx.x >= M.end[i]) ? 1 : 0;
   const ChainArgs* chain = nullptr;
   if constexpr (TP::HAS_CHAIN) chain = &M.chain;
-  run_slice(M.s[z], (int)blockIdx.x - (z ? M.end[z - 1] : 0), chain);
+  run_slice<W>(M.s[z], (int)blockIdx.x - (z ? M.end[z - 1] : 0), chain);
 }
 // Two builds of the same kernel.  With its scalar registers capped at 96 the kernel takes 67-72 vector registers:
 // seven workgroups per CU.  The dense build is held to 64 (eight workgroups per CU) and pays for it with more scalar
 // registers parked in vector lanes.  Launches of several times the chip's capacity gain from the eighth workgroup
 // (65,536-seed steps -4 %, the seven-relation workload -1.5 %); ordinary ticks, whose time is set by the dependent
 // chains of a few narrow slices, lose 3-6 % on the workloads with a refresh in the sample phase.
-template <class TP>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96))) void step_tick_kernel(TP M) { tick_body(M); }
+template <class TP, int W>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96))) void step_tick_kernel(TP M) { tick_body<TP, W>(M); }
 template <class TP>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96), amdgpu_waves_per_eu(8, 8))) void step_tick_dense_kernel(TP M) {
-  tick_body(M);
+  tick_body<TP, 32>(M);
 }
 // The compact form for one-relation graphs: the slice's full arguments are put together from the launch's shared
 // part, the slice's own part and the slot's entry of the device table (one more scalar load at the start).
@@ -1273,7 +1303,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96))) void step
   H.type[0].key_off = M.h.key_off; H.type[0].n_nodes = M.h.n_nodes;
   H.type[0].count_override = c.count_override; H.type[0].frontier_cap = c.frontier_cap;
   H.relc[0] = M.h.relc;
-  run_slice(H, (int)blockIdx.x - (z ? M.end[z - 1] : 0));
+  run_slice<32>(H, (int)blockIdx.x - (z ? M.end[z - 1] : 0));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1465,21 +1495,24 @@ static inline unsigned clamp_grid(int64_t want, int64_t cap) {
 hipError_t launch_fill_full(const FillParams& P, hipStream_t st, LaunchTimer* timer) {
   const unsigned grid = clamp_grid((P.n_dst + FILL_CHUNK - 1) / FILL_CHUNK, 8192);
   hipEvent_t start = nullptr, stop = nullptr;
+  void (*const kernel)(FillParams) = P.k > 32 ? fill_full_kernel<64> : fill_full_kernel<32>;   // rows wider than half a wavefront
   if (timer && timer->bracket(KID_FILL_FULL, &start, &stop))      // the events get the dispatch's own start / end times
-    hipExtLaunchKernelGGL(fill_full_kernel, dim3(grid), dim3(256), 0, st, start, stop, 0, P);
+    hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, st, start, stop, 0, P);
   else
-    hipLaunchKernelGGL(fill_full_kernel, dim3(grid), dim3(256), 0, st, P);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, st, P);
   return hipGetLastError();
 }
 
 hipError_t launch_fill_heavy(const FillParams& P, const int32_t* heavy, int64_t nheavy, hipStream_t st, LaunchTimer* timer) {
   if (nheavy <= 0) return hipSuccess;
-  const unsigned grid = clamp_grid((nheavy * P.ntab + 7) / 8, 16384);
+  const int groups = P.k > 32 ? 4 : 8;
+  const unsigned grid = clamp_grid((nheavy * P.ntab + groups - 1) / groups, 16384);
   hipEvent_t start = nullptr, stop = nullptr;
+  void (*const kernel)(FillParams, const int32_t*, int64_t) = P.k > 32 ? fill_heavy_kernel<64> : fill_heavy_kernel<32>;
   if (timer && timer->bracket(KID_FILL_FULL, &start, &stop))
-    hipExtLaunchKernelGGL(fill_heavy_kernel, dim3(grid), dim3(256), 0, st, start, stop, 0, P, heavy, nheavy);
+    hipExtLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, st, start, stop, 0, P, heavy, nheavy);
   else
-    hipLaunchKernelGGL(fill_heavy_kernel, dim3(grid), dim3(256), 0, st, P, heavy, nheavy);
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(256), 0, st, P, heavy, nheavy);
   return hipGetLastError();
 }
 
@@ -1518,7 +1551,10 @@ static hipError_t launch_tick_t(const HopParams* P, int n, const RelConst* relc_
     M.end[i] = total;
   }
   hipEvent_t start = nullptr, stop = nullptr;
-  void (*const kernel)(TP) = dense ? step_tick_dense_kernel<TP> : step_tick_kernel<TP>;
+  // rows of more than 32 slots: the build with one node per wavefront (it has no dense variant, and no chain code)
+  const bool wide = P[0].k > 32;
+  if (wide && TP::HAS_CHAIN) return hipErrorInvalidValue;
+  void (*const kernel)(TP) = wide ? step_tick_kernel<TP, 64> : dense ? step_tick_dense_kernel<TP> : step_tick_kernel<TP, 32>;
   if (timer && timer->bracket(KID_STEP_TICK, &start, &stop))
     hipExtLaunchKernelGGL(kernel, dim3((unsigned)total), dim3(256), 0, st, start, stop, 0, M);
   else if (done)   // the dispatch itself completes the event: no separate marker between this launch and the next
@@ -1591,7 +1627,7 @@ hipError_t launch_tick(const HopParams* P, int n, const RelConst* relc_host, con
   }
   if (chain) return hipErrorInvalidValue;
   if (R == 1 && T == 1 && n > 12) {
-    if (!slots_dev) return hipErrorInvalidValue;
+    if (!slots_dev || P[0].k > 32) return hipErrorInvalidValue;   // (the compact form has no build for wide rows)
     return launch_tick_mono(P, n, relc_host, slots_dev, st, timer, done);
   }
   if (R == 1 && T == 1) {

@@ -19,7 +19,7 @@ GSS_OK, GSS_ERR_INVALID_ARG, GSS_ERR_INVALID_GRAPH, GSS_ERR_INVALID_SEED = 0, 1,
 GSS_ERR_OOM, GSS_ERR_DEVICE, GSS_ERR_STEP_ORDER = 4, 5, 6
 GSS_MODE_FCR, GSS_MODE_OTF, GSS_MODE_SHARED_OTF, GSS_MODE_FBL, GSS_MODE_SHARED_FCR, GSS_MODE_OTF_FETCH, GSS_MODE_OTF_LAYER = \
     0, 1, 2, 3, 4, 5, 6
-GSS_MAX_K = 32
+GSS_MAX_K = 64
 GSS_MAX_IN_FLIGHT = 32
 
 EXPORTS = ["gss_create", "gss_create_tuned", "gss_step", "gss_destroy", "gss_cache_read", "gss_cache_checksum",

@@ -41,7 +41,7 @@ def test_host_side_argument_checks_need_no_device():
     nn = (ctypes.c_int64 * 1)(10)
     rel = (gss.gss_relation * 1)(gss.gss_relation(0, 0, 0, 1, 0, None))
     g = gss.gss_graph(1, nn, 1, rel)
-    for k, layers, mode, period in [(0, 1, 0, 1), (33, 1, 0, 1), (4, 0, 0, 1), (4, 9, 0, 1), (4, 1, 7, 1), (4, 1, 0, 0)]:
+    for k, layers, mode, period in [(0, 1, 0, 1), (65, 1, 0, 1), (4, 0, 0, 1), (4, 9, 0, 1), (4, 1, 7, 1), (4, 1, 0, 0)]:
         cfg = gss.gss_config(k, mode, layers, 0.0, period, 0, None, gss.ALLOC_FN(0), gss.FREE_FN(0), None)
         assert lib.gss_create(ctypes.byref(g), ctypes.byref(cfg), ctypes.byref(h)) == gss.GSS_ERR_INVALID_ARG
     bad = gss.gss_graph(1, nn, 1, (gss.gss_relation * 1)(gss.gss_relation(0, 3, 0, 1, 0, None)))

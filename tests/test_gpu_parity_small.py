@@ -518,3 +518,43 @@ def test_visit_once_steps_mixed_with_hop_by_hop_steps(tuning):
             s.step(torch.tensor(bad, dtype=torch.int32, device="cuda"), [3, 3, 3], 0)
         assert e.value.status == gss.GSS_ERR_INVALID_SEED
         s.close()
+
+
+WIDE_CASES = [
+    # k, mode, fraction, period, fanouts, batch: rows of 33 .. 64 slots take a whole wavefront per node
+    (33, OTF, 0.25, 1, [33, 7], 60),
+    (48, FCR, 0.0, 3, [20, 20, 20], 100),
+    (60, SHARED, 0.1, 1, [20, 20, 20], 120),
+    (64, OTF, 0.2, 1, [64, 1], 40),
+    (64, OTF, 1.0, 1, [30, 40], 77),
+    (40, SHARED, 0.3, 2, [20, 15], 150),
+    (64, FBL, 0.0, 1, [64, 33], 50),
+    (40, FBL, 0.0, 1, [20, 20, 20], 90),
+    (60, SHARED_FCR, 0.0, 2, [20, 20, 20], 100),
+    (48, OTF_FETCH, 0.4, 1, [40, 10], 80),
+    (64, OTF_FETCH, 1.0, 1, [33, 64], 30),
+    (36, OTF_LAYER, 0.25, 2, [36, 5], 60),
+    (64, OTF_LAYER, 0.5, 1, [10, 20], 90),
+]
+
+
+@pytest.mark.parametrize("k,mode,frac,period,fanouts,batch", WIDE_CASES)
+@pytest.mark.parametrize("indptr64", [False, True])
+def test_parity_rows_wider_than_half_a_wavefront(k, mode, frac, period, fanouts, batch, indptr64):
+    # a denser graph, so that all three degree regimes (deg <= k, k < deg < 2k, deg >= 2k) occur at these widths
+    g = synth.chunglu_graph(2500, 90000, 2.1, 5, indptr64=indptr64)
+    kw = dict(k=k, mode=mode, num_layers=len(fanouts), refresh_fraction=frac, refresh_period=period, rng_seed=987654321)
+    assert run_parity(g, kw, fanouts, batch, steps=[0, 1, 2, 3, 5, 6]) > 0
+    assert run_parity_pipelined(g, kw, fanouts, batch, steps=range(16)) > 0
+
+
+def test_wide_rows_degree_split_and_typed_graph():
+    g = synth.chunglu_graph(2500, 90000, 2.1, 5)
+    for mode, frac in [(OTF, 0.25), (SHARED, 0.25), (FCR, 0.0)]:
+        kw = dict(k=40, mode=mode, num_layers=2, refresh_fraction=frac, refresh_period=2, rng_seed=77, degree_threshold=50)
+        assert run_parity(g, kw, [20, 20], 200, steps=range(4)) > 0
+    gt = synth.hetero_graph([1200, 2000, 60, 300], [(1, 2, 26000), (1, 0, 90000), (0, 0, 50000), (0, 3, 80000)], 2.2, seed=8)
+    for mode, frac, k, fan in [(OTF, 0.2, 50, [50, 20]), (SHARED, 0.2, 64, [30, 30]), (FBL, 0.0, 40, [40, 20])]:
+        kw = dict(k=k, mode=mode, num_layers=2, refresh_fraction=frac, refresh_period=1, rng_seed=3)
+        assert run_parity(gt, kw, fan, 100, steps=range(4)) > 0
+        assert run_parity_pipelined(gt, kw, fan, 100, steps=range(10)) > 0
