@@ -178,7 +178,10 @@ typedef struct {
                                    in gss_step, 2: always hop by hop                                                   */
   int32_t chain_workgroups;     /* visit-once steps: most workgroups of a chain phase, which stride over the hop's nodes
                                    (1..65536; default 4096)                                                           */
-  int32_t reserved[6];          /* must be 0                                                                          */
+  int32_t lds_dedupe;           /* 1: the insert and place phases first dedupe each tile of 1024 picks in an LDS hash
+                                   table and send only the tile's first pick of an id to the global dedupe table.
+                                   Default off: measured slower (profiles/lds_dedupe_stage_ab.txt)                     */
+  int32_t reserved[5];          /* must be 0                                                                          */
 } gss_tuning;
 
 /* gss_create with the layout choices of `tuning` (NULL: all defaults, which is what gss_create passes). */

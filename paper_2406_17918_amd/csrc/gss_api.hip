@@ -171,6 +171,7 @@ struct gss_sampler {
   int dense_policy = 0;                  // gss_tuning.tick_build - 0: launches of DENSE_TICK_WGS workgroups and more use the dense build; 1: all, 2: none
   uint32_t first_version = VERSION_FIRST;   // where a slot's dedupe-table version counter starts
   int tick_cap = 1;                      // slices one launch can carry
+  bool lds_stage = false;                // gss_tuning.lds_dedupe: the per-tile LDS stage of the dedupe
   int chain_wg_cap = 4096;               // most workgroups of a chain slice, which stride over the rest (the 4,096-seed workload: 2,048 +5 %, 8,192 +5 %)
   bool visit_once_forced = false;        // gss_tuning.visit_once == 1: also the steps of blocking calls
   bool blocking_call = false;            // inside gss_step
@@ -337,7 +338,8 @@ void fill_slice(gss_sampler* s, Slot& sl, int it, HopParams& P) {
   for (int q = 0; q < l; ++q) P.band_offset += sl.fanouts[q];
   P.num_tiles_ub = (int32_t)(sl.total_slots[h] / TILE);
   P.scan_in_emit = scans_in_emit(s, sl, h) ? 1 : 0;
-  P.insert_split = (int32_t)((sl.insert_hops >> h) & 1u);
+  // bit 0: the hop has an insert phase; bit 1: insert and place phases dedupe their tile in LDS first
+  P.insert_split = (int32_t)((sl.insert_hops >> h) & 1u) | (s->lds_stage ? 2 : 0);
   P.edge_count_off = (GSS_MAX_LAYERS + 1) * T;
   P.ver = sl.ver0 + (uint32_t)h;
   P.step = (uint32_t)sl.step;
@@ -630,7 +632,7 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   if (tn.dedupe_layout < 0 || tn.dedupe_layout > 2 || tn.table_sets < 0 || tn.table_sets > MAX_TABLE_SETS ||
       tn.pipeline_depth < 0 || tn.pipeline_depth > GSS_MAX_IN_FLIGHT || tn.steps_per_tick < 0 || tn.steps_per_tick > 2 ||
       tn.insert_phase < 0 || tn.insert_phase > 2 || tn.scan_phase < 0 || tn.scan_phase > 1 || tn.tick_build < 0 ||
-      tn.tick_build > 2 || tn.visit_once < 0 || tn.visit_once > 2 || tn.chain_workgroups < 0 || tn.chain_workgroups > 65536 || tn.first_dedupe_version >= VERSION_LAST)
+      tn.tick_build > 2 || tn.visit_once < 0 || tn.visit_once > 2 || tn.chain_workgroups < 0 || tn.chain_workgroups > 65536 || tn.lds_dedupe < 0 || tn.lds_dedupe > 1 || tn.first_dedupe_version >= VERSION_LAST)
     return early(GSS_ERR_INVALID_ARG, "invalid argument (tuning field out of range)");
   for (int32_t v : tn.reserved)
     if (v != 0) return early(GSS_ERR_INVALID_ARG, "invalid argument (tuning: reserved fields must be 0)");
@@ -691,6 +693,7 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   s->visit_once = c->mode == GSS_MODE_SHARED_OTF && s->R == 1 && s->T == 1 && s->k <= 32 && tn.visit_once != 2;
   if (s->visit_once) s->tick_cap = CHAIN_TICK_SLICES;
   if (tn.chain_workgroups) s->chain_wg_cap = tn.chain_workgroups;
+  s->lds_stage = tn.lds_dedupe == 1;
   s->visit_once_forced = tn.visit_once == 1;
   for (float& r : s->fill_ratio) r = 1.0f;
   // Dedupe table layout: one 8-byte word per node (no probing, one atomic per insert) unless that

@@ -707,10 +707,51 @@ __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLdsT
     if (sel) {
       const uint32_t g = g0 + (uint32_t)mask_popc(selm & G.below());
       P.picks[g] = val;
-      if (!P.insert_split) table_insert_min(P.ht, P.ver, src_key_off + (uint32_t)val, EDGE_BIT | g, P.state);
+      if (!(P.insert_split & 1)) table_insert_min(P.ht, P.ver, src_key_off + (uint32_t)val, EDGE_BIT | g, P.state);
     }
     if (sub >= cnt && sub < f) P.picks[g0 + sub] = -1;
   }
+}
+
+// Optional first stage of the dedupe, per tile, in LDS ("LDS-staged unique, spilling to the global table"): the tile's
+// picks enter an open-addressing table of 2 * TILE 64-bit words, (key << 32) | slot within the tile, reduced with
+// a 64-bit LDS minimum; only the pick that holds the smallest slot of its id within the tile goes on to the global
+// table - the others could not win there anyway.  Returns, per thread, which of its ITEMS_PER_THREAD picks go on.
+// All threads of the workgroup call it (barriers inside); `key[q]` is only read where `valid` has bit q set.
+constexpr int TILE_HASH = 2 * TILE;
+struct DedupeLds { unsigned long long word[TILE_HASH]; };
+__device__ __forceinline__ uint32_t tile_firsts(DedupeLds* D, const uint32_t* key, uint32_t valid, uint32_t slot0) {
+  unsigned long long* tab = D->word;
+  for (int i = (int)threadIdx.x; i < TILE_HASH; i += (int)blockDim.x) tab[i] = ~0ull;
+  __syncthreads();
+  uint32_t home[ITEMS_PER_THREAD];
+#pragma unroll
+  for (int q = 0; q < ITEMS_PER_THREAD; ++q) {
+    home[q] = 0u;
+    if (!((valid >> q) & 1u)) continue;
+    const unsigned long long mine = ((unsigned long long)key[q] << 32) | (slot0 + (uint32_t)q);
+    uint32_t h = (key[q] * 0x9E3779B1u) >> 21;                    // 11 bits: TILE_HASH entries
+    for (;;) {                                                    // (at most TILE of the 2 TILE entries are ever taken)
+      unsigned long long cur = __hip_atomic_load(&tab[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+      if (cur == ~0ull &&                                         // empty: try to take it (on failure `cur` = who did)
+          __hip_atomic_compare_exchange_strong(&tab[h], &cur, mine, __ATOMIC_RELAXED, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP))
+        break;                                                    // taken: this pick is the smallest so far
+      if ((uint32_t)(cur >> 32) == key[q]) {
+        __hip_atomic_fetch_min(&tab[h], mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        break;
+      }
+      h = (h + 1u) & (uint32_t)(TILE_HASH - 1);
+    }
+    home[q] = h;
+  }
+  __syncthreads();
+  uint32_t first = 0u;
+#pragma unroll
+  for (int q = 0; q < ITEMS_PER_THREAD; ++q)
+    if (((valid >> q) & 1u) && (uint32_t)__hip_atomic_load(&tab[home[q]], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) == slot0 + (uint32_t)q)
+      first |= 1u << q;
+  __syncthreads();                                                // (the table is cleared again for the next tile)
+  return first;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -905,7 +946,7 @@ __device__ __forceinline__ void chain_phase(const HP& P, const ChainArgs& C, con
 // the holding area (through the node's holding index in the visit table) and enters it into the dedupe table; rows
 // wg.y >= 1 of the slice handle the dst nodes.  From here on the hop looks like any other: mark, emit.
 template <class HP>
-__device__ __forceinline__ void place_phase(const HP& P, const Wg wg, LiveLds* live) {
+__device__ __forceinline__ void place_phase(const HP& P, const Wg wg, LiveLds* live, DedupeLds* D) {
   if (wg.y >= 1) {
     dst_node_rows(P, 0, wg.x);
     return;
@@ -913,11 +954,11 @@ __device__ __forceinline__ void place_phase(const HP& P, const Wg wg, LiveLds* l
   live_tiles_setup(P, live);
   const TypeParam& TP = type_of(P, 0);
   const uint32_t f = (uint32_t)P.f;
+  const bool staged = (P.insert_split & 2) != 0;
   for (int j = wg.x; j < live->first[1]; j += P.gx) {
     const LiveTile lt = live_tile(P, live, j);
     const uint32_t nslots = lt.nslots;
     const uint32_t g = lt.local0 + ITEMS_PER_THREAD * threadIdx.x;       // one relation: its slots start at 0
-    if (g >= nslots) continue;
     uint32_t i = g / f, jj = g - i * f;
     int id[ITEMS_PER_THREAD];
     uint32_t Q = 0;
@@ -940,11 +981,17 @@ __device__ __forceinline__ void place_phase(const HP& P, const Wg wg, LiveLds* l
       }
       if (++jj == f) { jj = 0u; ++i; }
     }
-    *reinterpret_cast<int4*>(P.picks + g) = make_int4(id[0], id[1], id[2], id[3]);
-    const uint32_t key_off = TP.key_off;
+    if (g < nslots) *reinterpret_cast<int4*>(P.picks + g) = make_int4(id[0], id[1], id[2], id[3]);
+    uint32_t key[ITEMS_PER_THREAD], go = 0u;
+#pragma unroll
+    for (int q = 0; q < ITEMS_PER_THREAD; ++q) {
+      key[q] = TP.key_off + (uint32_t)id[q];
+      if (id[q] >= 0) go |= 1u << q;
+    }
+    if (staged) go = tile_firsts(D, key, go, ITEMS_PER_THREAD * threadIdx.x);
 #pragma unroll
     for (int q = 0; q < ITEMS_PER_THREAD; ++q)
-      if (id[q] >= 0) table_insert_min(P.ht, P.ver, key_off + (uint32_t)id[q], EDGE_BIT | (g + q), P.state);
+      if ((go >> q) & 1u) table_insert_min(P.ht, P.ver, key[q], EDGE_BIT | (g + q), P.state);
   }
 }
 
@@ -954,7 +1001,7 @@ __device__ __forceinline__ void place_phase(const HP& P, const Wg wg, LiveLds* l
 // table accesses in flight - in the sample phase the insert is the tail of a long dependent chain.
 // ------------------------------------------------------------------------------------------
 template <class HP>
-__device__ __forceinline__ void insert_phase(const HP& P, const Wg wg, LiveLds* live) {
+__device__ __forceinline__ void insert_phase(const HP& P, const Wg wg, LiveLds* live, DedupeLds* D) {
   // The workgroup's first tile is requested before the live counts are known (if it lies in relation 0 its
   // address does not depend on them, and the buffer covers every tile of the grid): the picks travel while the
   // counts are fetched.
@@ -962,19 +1009,27 @@ __device__ __forceinline__ void insert_phase(const HP& P, const Wg wg, LiveLds* 
   if (wg.x < P.num_tiles_ub)
     pv_first = *reinterpret_cast<const int4*>(P.picks + (uint32_t)rel_of(P, 0).slot_base + (uint32_t)wg.x * TILE + 4u * threadIdx.x);
   live_tiles_setup(P, live);
+  const bool staged = (P.insert_split & 2) != 0;
   for (int j = wg.x; j < live->first[P.R]; j += P.gx) {
     const LiveTile lt = live_tile(P, live, j);
     const RelParam& RP = rel_of(P, lt.r);
     const uint32_t nslots = lt.nslots;
     const uint32_t loc = lt.local0 + 4u * threadIdx.x;
     const uint32_t g = (uint32_t)RP.slot_base + loc;
-    if (loc >= nslots) continue;
-    const int4 pv = (j == wg.x && lt.r == 0) ? pv_first : *reinterpret_cast<const int4*>(P.picks + g);
+    int4 pv = make_int4(-1, -1, -1, -1);
+    if (loc < nslots) pv = (j == wg.x && lt.r == 0) ? pv_first : *reinterpret_cast<const int4*>(P.picks + g);
     const uint32_t key_off = type_of(P, RP.src_type).key_off;
     const int id[4] = {pv.x, pv.y, pv.z, pv.w};
+    uint32_t key[4], go = 0u;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-      if (loc + j < nslots && id[j] >= 0) table_insert_min(P.ht, P.ver, key_off + (uint32_t)id[j], EDGE_BIT | (g + j), P.state);
+    for (int q = 0; q < 4; ++q) {
+      key[q] = key_off + (uint32_t)id[q];
+      if (loc + q < nslots && id[q] >= 0) go |= 1u << q;
+    }
+    if (staged) go = tile_firsts(D, key, go, 4u * threadIdx.x);
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if ((go >> q) & 1u) table_insert_min(P.ht, P.ver, key[q], EDGE_BIT | (g + q), P.state);
   }
 }
 
@@ -1217,6 +1272,7 @@ union TickLds {
   GroupLdsT<W> group[256 / W];
   int scan[32];
   EmitLds emit;
+  DedupeLds dedupe;
 };
 // Scalar registers, not vector registers or LDS, decide how many workgroups a CU holds: with the 106 the
 // compiler takes by itself 6 were resident per CU (measured: 191 per XCD at the peak of a full tick), capped at
@@ -1241,11 +1297,11 @@ __device__ __forceinline__ void run_slice(const HP& P, int block, const ChainArg
     case PH_SAMPLE: sample_phase(P, wg, lds.group); break;
     case PH_MARK:   mark_phase(P, wg, lds.scan, &live); break;
     case PH_SCAN:   scan_phase(P, lds.scan, &live); break;
-    case PH_INSERT: insert_phase(P, wg, &live); break;
+    case PH_INSERT: insert_phase(P, wg, &live, &lds.dedupe); break;
     case PH_EMIT:   emit_phase(P, wg, &lds.emit, &live); break;
     default:
       if constexpr (std::is_same<HP, HopParamsChain>::value && W == 32) {     // (only this build holds the visit-once code)
-        if (P.phase == PH_PLACE) place_phase(P, wg, &live);
+        if (P.phase == PH_PLACE) place_phase(P, wg, &live, &lds.dedupe);
         else if (P.phase == PH_CHAIN) chain_phase(P, *C, wg, lds.group, &chain_lds);
       }
       break;

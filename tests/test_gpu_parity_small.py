@@ -558,3 +558,17 @@ def test_wide_rows_degree_split_and_typed_graph():
         kw = dict(k=k, mode=mode, num_layers=2, refresh_fraction=frac, refresh_period=1, rng_seed=3)
         assert run_parity(gt, kw, fan, 100, steps=range(4)) > 0
         assert run_parity_pipelined(gt, kw, fan, 100, steps=range(10)) > 0
+
+
+@pytest.mark.parametrize("k,mode,frac,period,fanouts,batch", [c for c in CASES if c[0] in (20, 30, 32, 9, 12)])
+def test_parity_with_the_lds_stage_of_the_dedupe(k, mode, frac, period, fanouts, batch, tuning):
+    # every hop gets an insert phase, and the insert phases (and the place phases of visit-once steps) first dedupe
+    # their tile of 1024 picks in LDS: only the tile's first pick of an id goes on to the global table
+    tuning(lds_dedupe=1, insert_phase=1, visit_once=1)
+    g = graph_small()
+    kw = dict(k=k, mode=mode, num_layers=len(fanouts), refresh_fraction=frac, refresh_period=period, rng_seed=2718)
+    assert run_parity(g, kw, fanouts, batch, steps=[0, 1, 2, 5]) > 0
+    assert run_parity_pipelined(g, kw, fanouts, batch, steps=range(20)) > 0
+    gt = synth.hetero_graph([1200, 2000, 60, 300], [(1, 2, 2600), (1, 0, 9000), (0, 0, 5000), (0, 3, 8000)], 2.2, seed=8)
+    if mode in (OTF, FCR) and len(fanouts) == 2:
+        assert run_parity_pipelined(gt, kw, fanouts, 100, steps=range(8)) > 0
