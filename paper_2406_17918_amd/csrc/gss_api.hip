@@ -693,7 +693,10 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   s->visit_once = c->mode == GSS_MODE_SHARED_OTF && s->R == 1 && s->T == 1 && s->k <= 32 && tn.visit_once != 2;
   if (s->visit_once) s->tick_cap = CHAIN_TICK_SLICES;
   if (tn.chain_workgroups) s->chain_wg_cap = tn.chain_workgroups;
-  s->lds_stage = tn.lds_dedupe == 1;
+  // (the stage lives in builds of the step kernel of their own: one-relation graphs with rows of up to 32 slots, one
+  // step per launch; elsewhere the field is ignored)
+  s->lds_stage = tn.lds_dedupe == 1 && s->R == 1 && s->T == 1 && s->k <= 32;
+  if (s->lds_stage && !s->visit_once) s->tick_cap = 12;
   s->visit_once_forced = tn.visit_once == 1;
   for (float& r : s->fill_ratio) r = 1.0f;
   // Dedupe table layout: one 8-byte word per node (no probing, one atomic per insert) unless that
@@ -716,6 +719,7 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   // twice as large) and keep one step per tick.
   s->steps_per_tick = (!s->otf && !s->fcr && s->R == 1 && s->T == 1 && s->k <= 32) ? 2 : 1;
   if (tn.steps_per_tick) s->steps_per_tick = (!s->otf && s->k <= 32 && tn.steps_per_tick == 2) ? 2 : 1;
+  if (s->lds_stage) s->steps_per_tick = 1;
   // A step of L hops has up to 4 L phases, one per launch: with two more steps than that in flight the step a
   // caller waits for has left the queue before.  (Deeper rings only widen the memory the launches touch: every slot
   // has scratch and a dedupe table of its own - 4 L + 4 was 1 % slower on the 1,024-seed workloads, 4 L too shallow.)

@@ -166,7 +166,8 @@ using HopParamsMid = HopParamsT<8, 4>;
 // (Samplers that run visit-once steps use a build of the step kernel of their own, whose launches carry the arguments
 // of a chain slice - at most one each, as chain phases of different steps never share a launch.  The other builds
 // hold none of that code: it costs them registers.)
-struct HopParamsChain : HopParamsMono {};     // the same slice in a launch that also carries a chain's arguments
+struct HopParamsStaged : HopParamsMono {};    // the same slice in the build whose insert phases hold the LDS stage of the dedupe
+struct HopParamsChain : HopParamsStaged {};   // ... and in launches that also carry a chain's arguments
 template <class HP> struct ChainOf { static constexpr bool HAS_CHAIN = false; };
 template <> struct ChainOf<HopParamsChain> { static constexpr bool HAS_CHAIN = true; ChainArgs chain; };
 template <class HP, int D>

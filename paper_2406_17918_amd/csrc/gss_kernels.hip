@@ -122,7 +122,6 @@ struct GrpT {
   __device__ __forceinline__ bool in(Mask m) const { return ((m >> sub) & (Mask)1) != 0; }       // is this lane's bit set
   __device__ __forceinline__ static Mask first(int n) { return n >= W ? ~(Mask)0 : (((Mask)1 << n) - (Mask)1); }
 };
-constexpr int GRP = 32;
 using GroupLds = GroupLdsT<32>;
 using Grp = GrpT<32>;
 using GroupLdsPtr = Grp::LdsPtr;
@@ -140,6 +139,22 @@ __device__ __forceinline__ int grp_rank(const GrpT<W>& G, int n, uint64_t p) {
   int r = 0;
 #pragma unroll 4
   for (int i = 0; i < n; ++i) r += (G.L->prio[i] < p) ? 1 : 0;
+  return r;
+}
+// The same over the first n entries with n the same in every lane of the wavefront (a slot count of the launch, not of
+// the node): the loop counter stays in scalar registers and four entries are compared per round.  Entries from n up to the
+// next multiple of four must hold PRIO_NONE (every lane of a group stores its slot's priority, PRIO_NONE beyond the row).
+template <int W>
+__device__ __forceinline__ int grp_rank_uniform(const GrpT<W>& G, int n, uint64_t p) {
+  const int n4 = (__builtin_amdgcn_readfirstlane(n) + 3) & ~3;
+  int r = 0;
+  for (int i = 0; i < n4; i += 4) {
+    const uint64_t q0 = G.L->prio[i], q1 = G.L->prio[i + 1], q2 = G.L->prio[i + 2], q3 = G.L->prio[i + 3];
+    r += (q0 < p) ? 1 : 0;          // (one compare and one add-with-carry each)
+    r += (q1 < p) ? 1 : 0;
+    r += (q2 < p) ? 1 : 0;
+    r += (q3 < p) ? 1 : 0;
+  }
   return r;
 }
 template <int W>
@@ -290,7 +305,29 @@ __device__ __forceinline__ int grp_refresh_part(const GrpT<W>& G, int val, int k
   const MaskT<W> slots = GrpT<W>::first(k);
   const uint64_t e = (sub < k) ? priority(lo64(sb), (uint32_t)sub) : PRIO_NONE;
   G.L->prio[sub] = e;
-  const int er = grp_rank(G, k, e);
+  // The n_new slots of smallest priority.  Priorities are uniform 64-bit numbers, so the slots below the
+  // (n_new + 5) / k quantile nearly always include them: then a slot only has to be compared with those few (a slot
+  // above the mark has at least n_new slots below it and is not ranked at all).  The wavefront walks over the slots
+  // that are below the mark in either of its groups - a scalar loop; a slot above the mark in one's own group adds
+  // nothing to a rank below it.  If a group has fewer than n_new slots below the mark, every slot is ranked among all.
+  uint64_t mark = PRIO_NONE;
+  if (n_new + 5 < k) mark = (uint64_t)(uint32_t)(4294967040.0f * (float)(n_new + 5) / (float)k) << 32;
+  const bool low = e < mark;
+  const uint64_t wave_low = __ballot(low), wave_here = __ballot(sub == 0);
+  uint64_t scan = wave_low;
+  bool enough = __popcll((unsigned long long)wave_low) >= n_new;
+  if constexpr (W == 32) {
+    const uint32_t lo = (uint32_t)wave_low, hi = (uint32_t)(wave_low >> 32);
+    enough = (__popc(lo) >= n_new || !(wave_here & 1ull)) && (__popc(hi) >= n_new || !((wave_here >> 32) & 1ull));
+    scan = lo | hi;
+  }
+  int er;
+  if (enough) {
+    er = low ? 0 : k;
+    for (uint64_t m = scan; m != 0; m &= m - 1) er += (G.L->prio[__builtin_ctzll(m)] < e) ? 1 : 0;
+  } else {
+    er = grp_rank_uniform(G, k, e);
+  }
   evict = grp_ballot(G, sub < k && er < n_new);
   const MaskT<W> retained = slots & ~evict;
   if (deg < 2u * (uint32_t)k) {
@@ -666,7 +703,7 @@ __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLdsT
     } else {
       const uint64_t pp = (sub < len) ? priority(hi64(sb), (uint32_t)sub) : PRIO_NONE;
       G.L->prio[sub] = pp;
-      const int rank = grp_rank(G, len, pp);
+      const int rank = grp_rank_uniform(G, k, pp);       // (slots from len on hold PRIO_NONE)
       int start = 0;
       if (P.shared) start = min(P.band_offset, len - fdraw);
       sel = sub < len && rank >= start && rank < start + fdraw;
@@ -707,7 +744,9 @@ __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLdsT
     if (sel) {
       const uint32_t g = g0 + (uint32_t)mask_popc(selm & G.below());
       P.picks[g] = val;
-      if (!(P.insert_split & 1)) table_insert_min(P.ht, P.ver, src_key_off + (uint32_t)val, EDGE_BIT | g, P.state);
+      bool inserts = !P.insert_split;                  // (bit 1, the LDS stage, is only ever set in the staged builds)
+      if constexpr (std::is_base_of<HopParamsStaged, HP>::value) inserts = !(P.insert_split & 1);
+      if (inserts) table_insert_min(P.ht, P.ver, src_key_off + (uint32_t)val, EDGE_BIT | g, P.state);
     }
     if (sub >= cnt && sub < f) P.picks[g0 + sub] = -1;
   }
@@ -823,7 +862,7 @@ __device__ __forceinline__ int visit_node(const HP& P, const ChainArgs& C, const
   if (ranked) {
     const uint64_t pp = (sub < len) ? priority(hi64(sb), (uint32_t)sub) : PRIO_NONE;
     G.L->prio[sub] = pp;
-    rank = grp_rank(G, len, pp);
+    rank = grp_rank_uniform(G, k, pp);                  // (slots from len on hold PRIO_NONE)
   }
   for (int h = c; h < C.L; ++h) {
     const int f = C.f(h);
@@ -1000,7 +1039,7 @@ __device__ __forceinline__ void place_phase(const HP& P, const Wg wg, LiveLds* l
 // table word of its id with the pick's slot.  Four consecutive slots per thread, four independent
 // table accesses in flight - in the sample phase the insert is the tail of a long dependent chain.
 // ------------------------------------------------------------------------------------------
-template <class HP>
+template <bool STAGED, class HP>
 __device__ __forceinline__ void insert_phase(const HP& P, const Wg wg, LiveLds* live, DedupeLds* D) {
   // The workgroup's first tile is requested before the live counts are known (if it lies in relation 0 its
   // address does not depend on them, and the buffer covers every tile of the grid): the picks travel while the
@@ -1009,7 +1048,25 @@ __device__ __forceinline__ void insert_phase(const HP& P, const Wg wg, LiveLds* 
   if (wg.x < P.num_tiles_ub)
     pv_first = *reinterpret_cast<const int4*>(P.picks + (uint32_t)rel_of(P, 0).slot_base + (uint32_t)wg.x * TILE + 4u * threadIdx.x);
   live_tiles_setup(P, live);
-  const bool staged = (P.insert_split & 2) != 0;
+  if (!STAGED || (P.insert_split & 2) == 0) {
+    for (int j = wg.x; j < live->first[P.R]; j += P.gx) {
+      const LiveTile lt = live_tile(P, live, j);
+      const RelParam& RP = rel_of(P, lt.r);
+      const uint32_t nslots = lt.nslots;
+      const uint32_t loc = lt.local0 + 4u * threadIdx.x;
+      const uint32_t g = (uint32_t)RP.slot_base + loc;
+      if (loc >= nslots) continue;
+      const int4 pv = (j == wg.x && lt.r == 0) ? pv_first : *reinterpret_cast<const int4*>(P.picks + g);
+      const uint32_t key_off = type_of(P, RP.src_type).key_off;
+      const int id[4] = {pv.x, pv.y, pv.z, pv.w};
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (loc + q < nslots && id[q] >= 0) table_insert_min(P.ht, P.ver, key_off + (uint32_t)id[q], EDGE_BIT | (g + q), P.state);
+    }
+    return;
+  }
+  // with the LDS stage: every thread of the workgroup takes part in every tile (barriers)
+  if constexpr (STAGED)
   for (int j = wg.x; j < live->first[P.R]; j += P.gx) {
     const LiveTile lt = live_tile(P, live, j);
     const RelParam& RP = rel_of(P, lt.r);
@@ -1026,7 +1083,7 @@ __device__ __forceinline__ void insert_phase(const HP& P, const Wg wg, LiveLds* 
       key[q] = key_off + (uint32_t)id[q];
       if (loc + q < nslots && id[q] >= 0) go |= 1u << q;
     }
-    if (staged) go = tile_firsts(D, key, go, 4u * threadIdx.x);
+    go = tile_firsts(D, key, go, 4u * threadIdx.x);
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       if ((go >> q) & 1u) table_insert_min(P.ht, P.ver, key[q], EDGE_BIT | (g + q), P.state);
@@ -1272,8 +1329,8 @@ union TickLds {
   GroupLdsT<W> group[256 / W];
   int scan[32];
   EmitLds emit;
-  DedupeLds dedupe;
 };
+static_assert(sizeof(DedupeLds) <= sizeof(EmitLds), "the LDS stage of the dedupe borrows the emit phase's scratch");
 // Scalar registers, not vector registers or LDS, decide how many workgroups a CU holds: with the 106 the
 // compiler takes by itself 6 were resident per CU (measured: 191 per XCD at the peak of a full tick), capped at
 // 96 it is 7 (223 per XCD); the spills go to lanes of a vector register.  Capping further for 8 costs more in
@@ -1297,18 +1354,24 @@ __device__ __forceinline__ void run_slice(const HP& P, int block, const ChainArg
     case PH_SAMPLE: sample_phase(P, wg, lds.group); break;
     case PH_MARK:   mark_phase(P, wg, lds.scan, &live); break;
     case PH_SCAN:   scan_phase(P, lds.scan, &live); break;
-    case PH_INSERT: insert_phase(P, wg, &live, &lds.dedupe); break;
+    case PH_INSERT: insert_phase<std::is_base_of<HopParamsStaged, HP>::value>(P, wg, &live, reinterpret_cast<DedupeLds*>(&lds.emit)); break;
     case PH_EMIT:   emit_phase(P, wg, &lds.emit, &live); break;
     default:
       if constexpr (std::is_same<HP, HopParamsChain>::value && W == 32) {     // (only this build holds the visit-once code)
-        if (P.phase == PH_PLACE) place_phase(P, wg, &live, &lds.dedupe);
+        if (P.phase == PH_PLACE) place_phase(P, wg, &live, reinterpret_cast<DedupeLds*>(&lds.emit));
         else if (P.phase == PH_CHAIN) chain_phase(P, *C, wg, lds.group, &chain_lds);
       }
       break;
   }
 }
 template <class TP, int W>
-__device__ __forceinline__ void tick_body(const TP& M) {
+__device__ __forceinline__ void tick_body(const TP& M_by_value) {
+  // The builds that carry a chain's arguments read their arguments where the launch put them, in the kernel argument
+  // segment (constant memory: scalar loads with run-time offsets), not through the by-value parameter: indexing that with
+  // the slice number made the compiler copy the whole structure to scratch memory there (from 8 slices on).  The other
+  // builds keep the parameter: with the pointer the 1,024-seed FCR workload ran 4 % slower.
+  typedef const __attribute__((address_space(4))) TP* KernargPtr;
+  const TP& M = TP::HAS_CHAIN ? *(const TP*)(KernargPtr)__builtin_amdgcn_kernarg_segment_ptr() : M_by_value;
   int z = 0;
 #pragma unroll
   for (int i = 0; i < TP::SLICES - 1; ++i) z += ((int)blockIdx.x >= M.end[i]) ? 1 : 0;
@@ -1609,8 +1672,12 @@ static hipError_t launch_tick_t(const HopParams* P, int n, const RelConst* relc_
   hipEvent_t start = nullptr, stop = nullptr;
   // rows of more than 32 slots: the build with one node per wavefront (it has no dense variant, and no chain code)
   const bool wide = P[0].k > 32;
-  if (wide && TP::HAS_CHAIN) return hipErrorInvalidValue;
-  void (*const kernel)(TP) = wide ? step_tick_kernel<TP, 64> : dense ? step_tick_dense_kernel<TP> : step_tick_kernel<TP, 32>;
+  void (*kernel)(TP) = dense ? step_tick_dense_kernel<TP> : step_tick_kernel<TP, 32>;
+  if constexpr (TP::HAS_CHAIN) {
+    if (wide) return hipErrorInvalidValue;
+  } else if (wide) {
+    kernel = step_tick_kernel<TP, 64>;
+  }
   if (timer && timer->bracket(KID_STEP_TICK, &start, &stop))
     hipExtLaunchKernelGGL(kernel, dim3((unsigned)total), dim3(256), 0, st, start, stop, 0, M);
   else if (done)   // the dispatch itself completes the event: no separate marker between this launch and the next
@@ -1682,6 +1749,10 @@ hipError_t launch_tick(const HopParams* P, int n, const RelConst* relc_host, con
     return launch_tick_t<HopParamsChain, CHAIN_TICK_SLICES>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
   }
   if (chain) return hipErrorInvalidValue;
+  if (P[0].insert_split & 2) {      // the sampler uses the LDS stage of the dedupe: a build of its own (one relation, rows of up to 32 slots)
+    if (R != 1 || T != 1 || n > 12 || P[0].k > 32) return hipErrorInvalidValue;
+    return launch_tick_t<HopParamsStaged, 12>(P, n, relc_host, relc_dev, nullptr, st, timer, done, dense);
+  }
   if (R == 1 && T == 1 && n > 12) {
     if (!slots_dev || P[0].k > 32) return hipErrorInvalidValue;   // (the compact form has no build for wide rows)
     return launch_tick_mono(P, n, relc_host, slots_dev, st, timer, done);
