@@ -27,6 +27,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+VALU_PEAK_GINST = 256 * 4 * 2.4 / 4   # G wavefront-wide 32-bit vector instructions per second: CUs x SIMDs x GHz / 4 cycles each
 
 
 def byte_model(w, indptr_bytes):
@@ -238,10 +239,11 @@ def run_oracle(w, graph, first_step, max_steps, budget_s):
 _TRAFFIC = None
 
 
-def recorded_traffic(workload, kernel, lib_version):
+def recorded_traffic(workload, kernel, lib_version, table="bytes_per_launch"):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE, each scaled by a plain copy of
     known size) - a RECORDED figure, kept in profiles/traffic.json together with the version string of the library
-    it was measured on; None when the library has changed since."""
+    it was measured on; None when the library has changed since.  table="valu_insts_per_launch" gives the
+    SQ_INSTS_VALU count of the same kind of run instead."""
     global _TRAFFIC
     if _TRAFFIC is None:
         try:
@@ -250,7 +252,7 @@ def recorded_traffic(workload, kernel, lib_version):
             _TRAFFIC = {}
     if _TRAFFIC.get("library_version") != lib_version:
         return None
-    return _TRAFFIC.get("bytes_per_launch", {}).get(workload, {}).get(kernel)
+    return _TRAFFIC.get(table, {}).get(workload, {}).get(kernel)
 
 
 def roofline_of(w, graph, res, lib_version):
@@ -283,7 +285,22 @@ def roofline_of(w, graph, res, lib_version):
                 impl_extra_bytes_per_launch=round(edges * m["impl_extra_per_edge"] / d["launches"], 1) if dom == "step_tick" else 0)
     kernels = {n: dict(avg_us=round(v["avg_us"], 3), launches=v["launches"], alg_gbs=round(v["gbs"], 3))
                for n, v in per_kernel.items()}
-    return roof, kernels
+    # The sampling phases are bound by vector-instruction issue, not by HBM: the same launches against that roof.
+    # achieved = VALU instructions issued per launch (SQ_INSTS_VALU, one count per wavefront instruction; recorded
+    # like `traffic`) / the launch duration measured here.  peak = 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per
+    # wavefront instruction (a SIMD has 16 lanes: a 64-wide wavefront takes 4 cycles per 32-bit vector instruction;
+    # the published 157.3 TFLOP/s of fp32 is this rate x 64 lanes x 2 flops x 2 for the packed forms).
+    alu = None
+    if "step_tick" in per_kernel:
+        t = per_kernel["step_tick"]
+        valu = recorded_traffic(w.name, "step_tick", lib_version, "valu_insts_per_launch")
+        rate = valu / (1e-6 * t["avg_us"]) / 1e9 if valu else None
+        alu = dict(bound="alu", kernel="step_tick", achieved=round(rate, 3) if rate else None, peak=VALU_PEAK_GINST,
+                   unit="G wavefront VALU instructions/s", frac=round(rate / VALU_PEAK_GINST, 6) if rate else None,
+                   valu_insts_per_launch=valu,
+                   valu_insts_per_visited_node=round(valu * t["launches"] / max(nodes, 1), 1) if valu else None,
+                   kind="recorded count (rocprofv3 --pmc SQ_INSTS_VALU, profiles/) over the live launch duration; null: none for this library version")
+    return roof, kernels, alu
 
 
 MODE_NAMES = ["FCR", "OTF", "SHARED_OTF", "FBL", "SHARED_FCR", "OTF_FETCH", "OTF_LAYER"]
@@ -293,7 +310,7 @@ def measure_workload(w, graph, steps, warmup, cpu_budget_s, lib_version):
     """Every figure of one workload (see run_gpu); the oracle leg is skipped when cpu_budget_s == 0."""
     steady_steps = max(steps, 200)
     res = run_gpu(w, graph, steps, warmup, profile_steps=max(steps, 100), steady_steps=steady_steps, blocking_steps=20)
-    roof, kernels = roofline_of(w, graph, res, lib_version)
+    roof, kernels, alu = roofline_of(w, graph, res, lib_version)
     indptr_bytes = graph.relations[0].indptr.itemsize
     step_bytes = algorithmic_bytes(w, res["prof_counts"], indptr_bytes) / max(res["prof_steps"], 1)
     st = res["steady"]
@@ -330,7 +347,7 @@ def measure_workload(w, graph, steps, warmup, cpu_budget_s, lib_version):
         "alg_bytes_per_step": round(step_bytes, 1),
         "cache_bytes": res["cache_bytes"],
         "cache_bytes_logical": logical_cache_bytes(w, graph),
-        "roofline": roof, "kernels": kernels, "cpu_baseline": cpu,
+        "roofline": roof, "roofline_alu": alu, "kernels": kernels, "cpu_baseline": cpu,
     }
 
 

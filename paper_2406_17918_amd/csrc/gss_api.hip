@@ -600,7 +600,7 @@ void destroy_impl(gss_sampler* s) {
 
 extern "C" {
 
-const char* gss_version(void) { return "gss 0.2 (gfx950)"; }
+const char* gss_version(void) { return "gss 0.3 (gfx950)"; }
 
 const char* gss_last_error(const gss_sampler* s) { return s ? s->err : g_create_err; }
 
