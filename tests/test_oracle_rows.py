@@ -45,7 +45,7 @@ class SeqRng:
 
 
 # ----------------------------------------------------------------- validity
-@pytest.mark.parametrize("k", [1, 4, 10, 20, 30])
+@pytest.mark.parametrize("k", [1, 4, 10, 20, 30, 33, 40, 64])
 def test_fill_full_validity(k):
     rs = np.random.default_rng(k)
     for trial in range(60):
@@ -74,7 +74,7 @@ def test_fill_full_depends_on_key_fields():
     assert np.array_equal(base, gsso.fill_full_row(philox(1), adj, 8, node=5))
 
 
-@pytest.mark.parametrize("k,n_new", [(10, 2), (20, 4), (30, 3), (25, 5), (4, 4), (6, 1)])
+@pytest.mark.parametrize("k,n_new", [(10, 2), (20, 4), (30, 3), (25, 5), (4, 4), (6, 1), (33, 3), (40, 8), (64, 6), (64, 64)])
 def test_refresh_part_validity(k, n_new):
     rs = np.random.default_rng(100 + k)
     for trial in range(80):
@@ -282,3 +282,21 @@ def test_refresh_then_pick_stays_uniform():
                     out = gsso.pick_row(prio_rng({gsso.PICK: pp}), row1, 2)
                     counts[frozenset(out.tolist())] += 1
     assert len(counts) == 10 and len(set(counts.values())) == 1
+
+
+@pytest.mark.parametrize("k,f,deg", [(40, 20, 90), (64, 20, 100), (64, 20, 70), (60, 20, 400)])
+def test_wide_rows_fill_then_pick_is_uniform_chi_square(k, f, deg):
+    # rows of 33-64 slots follow the same row functions; with the real generator, a full fill followed by the draw
+    # picks every neighbor equally often (both fill regimes: deg < 2k and deg >= 2k)
+    adj = np.arange(1000, 1000 + deg, dtype=np.int32)
+    count = Counter()
+    trials = 3000
+    for t in range(trials):
+        row = gsso.fill_full_row(philox(77), adj, k, node=5, stepword=t)
+        picks = gsso.pick_row(philox(77), row, f, node=5, step=t)
+        assert len(picks) == f and len(set(picks.tolist())) == f
+        count.update(picks.tolist())
+    exp = trials * f / deg
+    chi2 = sum((count.get(int(a), 0) - exp) ** 2 / exp for a in adj)
+    # chi-square with deg - 1 degrees of freedom: mean deg - 1, sd sqrt(2 (deg - 1)); 5 sd
+    assert chi2 < (deg - 1) + 5 * (2 * (deg - 1)) ** 0.5, chi2
