@@ -1021,6 +1021,7 @@ __device__ __forceinline__ void place_phase(const HP& P, const Wg wg, LiveLds* l
       if (++jj == f) { jj = 0u; ++i; }
     }
     if (g < nslots) *reinterpret_cast<int4*>(P.picks + g) = make_int4(id[0], id[1], id[2], id[3]);
+    if (P.insert_split & 1) continue;     // (uniform: the hop has an insert phase, which enters the picks into the table)
     uint32_t key[ITEMS_PER_THREAD], go = 0u;
 #pragma unroll
     for (int q = 0; q < ITEMS_PER_THREAD; ++q) {

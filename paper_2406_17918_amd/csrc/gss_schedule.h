@@ -26,15 +26,15 @@ struct StepItems {
 
   // hop h gets a separate scan phase iff bit h of `scan_hops` is set (hops with very many tiles), and a
   // separate insert phase iff bit h of `insert_hops` is set (large hops: the dedupe table inserts leave
-  // the sample phase, which shortens the longest phase of a launch).  `chain`: a visit-once step (its place
-  // phases do the inserts themselves).
+  // the sample phase - or the place phase of a visit-once step -, which shortens the longest phase of a launch).
+  // `chain`: a visit-once step.
   void build(int layers, uint32_t scan_hops, uint32_t insert_hops, bool chain = false) {
     L = layers; num_items = 0; next_item = 0;
     num_chain = chain ? layers : 0; next_chain = 0;
     auto push = [&](int h, Phase ph) { item_hop[num_items] = (int8_t)h; item_phase[num_items++] = (int8_t)ph; };
     for (int h = 0; h < layers; ++h) {
       push(h, chain ? PH_PLACE : PH_SAMPLE);
-      if (!chain && ((insert_hops >> h) & 1u)) push(h, PH_INSERT);
+      if ((insert_hops >> h) & 1u) push(h, PH_INSERT);
       push(h, PH_MARK);
       if ((scan_hops >> h) & 1u) push(h, PH_SCAN);
       push(h, PH_EMIT);

@@ -492,6 +492,18 @@ def test_shared_table_steps_both_ways(k, frac, period, fanouts, batch, theta, vi
     assert run_parity_pipelined(g, kw, fanouts, batch, steps=range(25)) > 0
 
 
+@pytest.mark.parametrize("k,frac,period,fanouts,batch,theta", SHARED_CASES)
+def test_visit_once_steps_with_insert_phases(k, frac, period, fanouts, batch, theta, tuning):
+    # the place phases only put the picks into frontier order; insert phases of their own enter them into the dedupe
+    # table (gss_tuning.insert_phase = 1; the library never chooses it by itself for these steps)
+    tuning(visit_once=1, insert_phase=1)
+    g = graph_small()
+    kw = dict(k=k, mode=SHARED, num_layers=len(fanouts), refresh_fraction=frac, refresh_period=period, rng_seed=4243,
+              degree_threshold=theta)
+    assert run_parity(g, kw, fanouts, batch, steps=[0, 1, 2, 3, 5, 8]) > 0
+    assert run_parity_pipelined(g, kw, fanouts, batch, steps=range(25)) > 0
+
+
 def test_visit_once_steps_mixed_with_hop_by_hop_steps(tuning):
     # steps of up to four hops run visit-once, a five-hop step between them hop by hop; batches of very different
     # sizes (the holding area grows), an empty batch, repeated and out-of-range seeds

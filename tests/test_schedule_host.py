@@ -31,10 +31,9 @@ def shim(tmp_path_factory):
 def items_of(layers, scan_hops, insert_hops=0, chain=False):
     out = []
     for h in range(layers):
-        if chain:                 # a visit-once step: the place phase does the inserts itself
-            out += [(h, PLACE), (h, MARK)]
-        else:
-            out += [(h, SAMPLE)] + ([(h, INSERT)] if (insert_hops >> h) & 1 else []) + [(h, MARK)]
+        # (a visit-once step has a place phase where the others have the sample phase; either does the dedupe table
+        # inserts itself unless the hop has an insert phase)
+        out += [(h, PLACE if chain else SAMPLE)] + ([(h, INSERT)] if (insert_hops >> h) & 1 else []) + [(h, MARK)]
         out += ([(h, SCAN)] if (scan_hops >> h) & 1 else []) + [(h, EMIT)]
     return out
 
@@ -188,6 +187,7 @@ def test_visit_once_steps(shim, seed):
             sim.wait_oldest()
         layers = int(rs.choice([1, 2, 3, 3, 4]))
         sim.enqueue(layers, scan_hops=int(rs.integers(0, 1 << layers)) if rs.random() < 0.3 else 0,
+                    insert_hops=int(rs.integers(0, 1 << layers)) if rs.random() < 0.4 else 0,
                     chain=bool(seed == 0 or rs.random() < 0.7))
     while sim.flight:
         sim.wait_oldest()
@@ -226,3 +226,17 @@ def test_visit_once_steps(shim, seed):
         assert [st["cat"][c] for c in range(3)] == [30, 31, 32]
         assert [st["at"][j] for j in range(9)] == [31, 32, 33, 36, 37, 38, 39, 40, 41]
         assert sim.ticks == 30 * 3 + 7                                        # (the last step drains without waiting)
+        # the same with an insert phase on the outermost hop: its place phase still joins a hop-0 tick, the insert
+        # phase the tick after (the chain phase of hop 1), and the step ends one tick later
+        sim = Sim(shim, otf=True, shared=True)
+        for step in range(30):
+            if len(sim.flight) == 8:
+                sim.wait_oldest()
+            sim.enqueue(3, insert_hops=0b100, chain=True)
+        while sim.flight:
+            sim.wait_oldest()
+        st = sim.steps[10]
+        assert st["items"][6:8] == [(2, PLACE), (2, INSERT)]
+        assert [st["cat"][c] for c in range(3)] == [30, 31, 32]
+        assert [st["at"][j] for j in range(10)] == [31, 32, 33, 36, 37, 38, 39, 40, 41, 42]
+        assert sim.ticks == 30 * 3 + 8
