@@ -166,7 +166,8 @@ typedef struct {
                                    where a launch starts two steps).  Every step in flight owns scratch, outputs and
                                    (direct layout) a dedupe table.                                                    */
   int32_t steps_per_tick;       /* 1 | 2: steps a launch starts (2 only in modes that never write a table)           */
-  int32_t insert_phase;         /* 1: every hop gets a separate insert phase, 2: none does                           */
+  int32_t insert_phase;         /* 1: every hop gets a separate insert phase (visit-once steps: after the place phase,
+                                   which they otherwise never get), 2: none does                                      */
   int32_t scan_phase;           /* 1: every hop gets a separate scan phase                                           */
   int32_t tick_build;           /* 1: every launch uses the step kernel's 8-workgroups-per-CU build, 2: none does     */
   uint32_t first_dedupe_version;/* start of each slot's dedupe-table version counter (tests of the wrap-around)       */
