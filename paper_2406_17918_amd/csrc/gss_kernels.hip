@@ -596,6 +596,15 @@ __device__ __forceinline__ void dst_node_rows(const HP& P, int t, int x) {
     const int v = TP.frontier[i];
     if ((uint32_t)v >= (uint32_t)TP.n_nodes) { atomicOr(&P.state[ST_ERROR], ERR_SEED_RANGE); continue; }
     TP.src_nodes[i] = v;
+    if (P.hop > 0 && P.ht.direct) {
+      // Beyond the seeds the dst nodes are distinct (the previous hop's dedupe made them so), and a frontier index is
+      // smaller than every pick's order word: whatever the picks of the same launch do to the node's word with their
+      // atomic minimum, before or after, a plain store of the frontier index leaves the minimum there.  (Random
+      // device-scope atomics run at 27 per ns on the whole chip, whatever the table size; plain stores at 50-180.)
+      __hip_atomic_store((unsigned long long*)&P.ht.direct[TP.key_off + (uint32_t)v], ((unsigned long long)(~P.ver) << 32) | (uint32_t)i,
+                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      continue;
+    }
     const uint32_t old = table_insert_min(P.ht, P.ver, TP.key_off + (uint32_t)v, (uint32_t)i, P.state);
     if (old < EDGE_BIT && old != (uint32_t)i) atomicOr(&P.state[ST_ERROR], ERR_SEED_DUP);
   }
