@@ -920,10 +920,23 @@ __device__ __forceinline__ void chain_phase(const HP& P, const ChainArgs& C, con
       CL->start[threadIdx.x + 1] = n < cap ? n : cap;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      uint32_t run = nseeds;
-      for (int q = 0; q < nsegs; ++q) { const uint32_t n = CL->start[q + 1]; CL->start[q] = run; run += n; }
-      CL->start[nsegs] = run;
+    if (threadIdx.x < 64) {
+      // exclusive prefix of the segment sizes (size of segment q at start[q + 1] -> its first item at start[q]) by the
+      // first wavefront, two segments per lane: a lane's stores depend, through the shuffles, on the loads of every
+      // lane below it, which are the only other readers of the words it overwrites
+      const int l = (int)threadIdx.x;
+      static_assert(CHAIN_MAX_HOPS * CHAIN_SEGS <= 128, "two segments per lane");
+      const uint32_t a = 2 * l < nsegs ? CL->start[2 * l + 1] : 0u, b = 2 * l + 1 < nsegs ? CL->start[2 * l + 2] : 0u;
+      uint32_t inc = a + b;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = (uint32_t)__shfl_up((int)inc, o);
+        if (l >= o) inc += t;
+      }
+      const uint32_t ex = nseeds + inc - (a + b);
+      if (2 * l < nsegs) CL->start[2 * l] = ex;
+      if (2 * l + 1 < nsegs) CL->start[2 * l + 1] = ex + a;
+      if (l == 63) CL->start[nsegs] = nseeds + inc;
     }
     __syncthreads();
   }
