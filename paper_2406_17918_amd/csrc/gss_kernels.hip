@@ -895,7 +895,7 @@ __device__ __forceinline__ int visit_node(const HP& P, const ChainArgs& C, const
 // c's picks of every frontier node - of the ones just visited, and of the nodes of earlier hops, whose picks are held -
 // then claim their nodes: a pick that comes first appends its node to list c + 1.
 struct ChainLds { uint32_t start[CHAIN_MAX_HOPS * CHAIN_SEGS + 2]; };
-template <class HP>
+template <bool AHEAD, class HP>
 __device__ __forceinline__ void chain_phase(const HP& P, const ChainArgs& C, const Wg wg, GroupLds* lds, ChainLds* CL) {
   Grp G;
   G.init(lds);
@@ -953,12 +953,20 @@ __device__ __forceinline__ void chain_phase(const HP& P, const ChainArgs& C, con
     return C.list[C.loff[h] + (uint32_t)(q % CHAIN_SEGS) * C.lcap[h] + (g - CL->start[q])];
   };
   int h_ahead = 0;
-  uint64_t e_ahead = (uint32_t)grp < total ? item((uint32_t)grp, h_ahead) : 0ull;
+  uint64_t e_ahead = (AHEAD && (uint32_t)grp < total) ? item((uint32_t)grp, h_ahead) : 0ull;
   for (uint32_t g = (uint32_t)grp; g < total; g += (uint32_t)ngrp) {
-    // ---- which node (the group's next item travels while this one is worked on) ----
-    const uint64_t e = e_ahead;
-    const int h = h_ahead;
-    if (g + (uint32_t)ngrp < total) e_ahead = item(g + (uint32_t)ngrp, h_ahead);
+    // ---- which node (the group's next item travels while this one is worked on - not in the build held to 64
+    //      vector registers, where the item in flight meant two registers spilled to scratch memory, and a kernel that
+    //      uses scratch memory is followed by 4.5 us of idle time before the next launch starts) ----
+    uint64_t e;
+    int h;
+    if constexpr (AHEAD) {
+      e = e_ahead;
+      h = h_ahead;
+      if (g + (uint32_t)ngrp < total) e_ahead = item(g + (uint32_t)ngrp, h_ahead);
+    } else {
+      e = item(g, h);
+    }
     const int v = (int)(uint32_t)e;
     const uint32_t Q = (uint32_t)(e >> 32);
     const bool fresh = h == c;                           // first reached by this hop: to be visited
@@ -1359,7 +1367,7 @@ static_assert(sizeof(DedupeLds) <= sizeof(EmitLds), "the LDS stage of the dedupe
 // 96 it is 7 (223 per XCD); the spills go to lanes of a vector register.  Capping further for 8 costs more in
 // spill code than the slots bring.
 // The workgroup `block` of the slice with arguments P.
-template <int W, class HP>
+template <int W, bool DENSE, class HP>
 __device__ __forceinline__ void run_slice(const HP& P, int block, const ChainArgs* C = nullptr) {
   // rows 0 .. gy-1 of the slice are gx workgroups wide, the gyd rows after them gxd (sample phase: the
   // rows of the node types need one thread per frontier node, not one 32-lane group)
@@ -1382,12 +1390,12 @@ __device__ __forceinline__ void run_slice(const HP& P, int block, const ChainArg
     default:
       if constexpr (std::is_same<HP, HopParamsChain>::value && W == 32) {     // (only this build holds the visit-once code)
         if (P.phase == PH_PLACE) place_phase(P, wg, &live, reinterpret_cast<DedupeLds*>(&lds.emit));
-        else if (P.phase == PH_CHAIN) chain_phase(P, *C, wg, lds.group, &chain_lds);
+        else if (P.phase == PH_CHAIN) chain_phase<!DENSE>(P, *C, wg, lds.group, &chain_lds);
       }
       break;
   }
 }
-template <class TP, int W>
+template <class TP, int W, bool DENSE = false>
 __device__ __forceinline__ void tick_body(const TP& M_by_value) {
   // The builds that carry a chain's arguments read their arguments where the launch put them, in the kernel argument
   // segment (constant memory: scalar loads with run-time offsets), not through the by-value parameter: indexing that with
@@ -1400,7 +1408,7 @@ __device__ __forceinline__ void tick_body(const TP& M_by_value) {
   for (int i = 0; i < TP::SLICES - 1; ++i) z += ((int)blockIdx.x >= M.end[i]) ? 1 : 0;
   const ChainArgs* chain = nullptr;
   if constexpr (TP::HAS_CHAIN) chain = &M.chain;
-  run_slice<W>(M.s[z], (int)blockIdx.x - (z ? M.end[z - 1] : 0), chain);
+  run_slice<W, DENSE>(M.s[z], (int)blockIdx.x - (z ? M.end[z - 1] : 0), chain);
 }
 // Two builds of the same kernel.  With its scalar registers capped at 96 the kernel takes 67-72 vector registers:
 // seven workgroups per CU.  The dense build is held to 64 (eight workgroups per CU) and pays for it with more scalar
@@ -1411,7 +1419,7 @@ template <class TP, int W>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96))) void step_tick_kernel(TP M) { tick_body<TP, W>(M); }
 template <class TP>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96), amdgpu_waves_per_eu(8, 8))) void step_tick_dense_kernel(TP M) {
-  tick_body<TP, 32>(M);
+  tick_body<TP, 32, true>(M);
 }
 // The compact form for one-relation graphs: the slice's full arguments are put together from the launch's shared
 // part, the slice's own part and the slot's entry of the device table (one more scalar load at the start).
@@ -1445,7 +1453,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96))) void step
   H.type[0].key_off = M.h.key_off; H.type[0].n_nodes = M.h.n_nodes;
   H.type[0].count_override = c.count_override; H.type[0].frontier_cap = c.frontier_cap;
   H.relc[0] = M.h.relc;
-  run_slice<32>(H, (int)blockIdx.x - (z ? M.end[z - 1] : 0));
+  run_slice<32, false>(H, (int)blockIdx.x - (z ? M.end[z - 1] : 0));
 }
 
 // ------------------------------------------------------------------------------------------
