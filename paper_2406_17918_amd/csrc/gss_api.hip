@@ -228,11 +228,12 @@ void dev_free(gss_sampler* s, void* p) {
 // When the allocation fails the buffer stays as it was.
 bool ensure(gss_sampler* s, Buf& b, size_t bytes) {
   if (b.bytes >= bytes && b.p) return true;
+  bytes = std::max<size_t>(bytes, 16);
   void* p = dev_alloc(s, bytes);
   if (!p) return false;
   dev_free(s, b.p);
   b.p = p;
-  b.bytes = std::max<size_t>(bytes, 16);
+  b.bytes = bytes;                       // (what was asked of the allocator, never more)
   return true;
 }
 void release(gss_sampler* s, Buf& b) { dev_free(s, b.p); b.p = nullptr; b.bytes = 0; }
@@ -724,8 +725,10 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   // caller waits for has left the queue before.  (Deeper rings only widen the memory the launches touch: every slot
   // has scratch and a dedupe table of its own - 4 L + 4 was 1 % slower on the 1,024-seed workloads, 4 L too shallow.)
   s->ring = std::min(GSS_MAX_IN_FLIGHT, s->steps_per_tick * (4 * s->L + 2));
-  // (a visit-once step of L hops is in flight for about 4 L launches, of which L are its own: L + 3 steps cover that)
-  if (s->visit_once) s->ring = std::min(GSS_MAX_IN_FLIGHT, s->L + 3);
+  // (a visit-once step's list phases trail its chain by a little more than three steps' worth of launches - the place
+  // phase of every hop past the first waits for the next step's first chain phase -: five steps in flight cover that
+  // for up to three hops; six were 0.6 % slower on the 4,096-seed shared-table workload, four 8 %)
+  if (s->visit_once) s->ring = std::min(GSS_MAX_IN_FLIGHT, std::max(5, s->L + 2));
   if (tn.pipeline_depth) s->ring = tn.pipeline_depth;
   if ((e = hipStreamCreateWithFlags(&s->work, hipStreamNonBlocking)) != hipSuccess) { s->work = nullptr; return hipfail(e); }
   for (hipEvent_t& ev : s->tick_ev)

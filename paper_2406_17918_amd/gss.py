@@ -172,7 +172,10 @@ class _TorchAllocator:
     def view_i32(self, ptr, n):
         if not ptr or n == 0:
             return self.torch.empty(0, dtype=self.torch.int32, device=self.device)
-        return self.live[int(ptr)][: 4 * n].view(self.torch.int32)
+        t = self.live[int(ptr)]
+        if t.numel() < 4 * n:              # (the library reported more elements than the buffer it asked for holds)
+            raise GssError(GSS_ERR_DEVICE, f"output of {n} int32 in an allocation of {t.numel()} bytes")
+        return t[: 4 * n].view(self.torch.int32)
 
 
 def upload_graph(graph, device="cuda:0") -> List[DeviceRelation]:

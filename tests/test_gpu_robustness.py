@@ -1,6 +1,7 @@
 """GPU tests of the host driver's failure handling and rarely taken paths: an allocator that runs out of memory
-(at gss_create and while a step's buffers grow), the wrap-around of the dedupe-table version counter, and the
-hashed dedupe layout at the size of the large workload.  Every kernel exits normally in all of them."""
+(at gss_create and while a step's buffers grow), buffers of a few bytes that grow by a few bytes, the wrap-around of
+the dedupe-table version counter, and the hashed dedupe layout at the size of the large workload.  Every kernel exits
+normally in all of them."""
 import numpy as np
 import pytest
 
@@ -115,3 +116,23 @@ def test_hashed_dedupe_layout_on_the_large_graph(tuning):
     total = run_parity(g, w, w.fanouts, w.batch, steps, workload_seed=w.workload_seed, full_cache_every=10**9)
     total2 = run_parity_pipelined(g, w, w.fanouts, w.batch, steps, workload_seed=w.workload_seed)
     assert total2 == total > 0
+
+
+@pytest.mark.parametrize("mode,frac", [(gsso.MODE_SHARED_OTF, 0.25), (gsso.MODE_OTF, 0.25), (gsso.MODE_FBL, 0.0)])
+def test_buffers_of_a_few_bytes_grow_by_a_few_bytes(mode, frac, tuning):
+    # one seed with fanout 2 makes output buffers of 8 bytes; the next steps on the same slot need 12, 16, 20 ... bytes
+    # (a buffer was once booked as 16 bytes where 8 had been asked of the allocator).  The binding refuses a block
+    # whose arrays do not fit the allocations they live in.
+    import torch
+    from paper_2406_17918_amd import gss
+    tuning(pipeline_depth=1)
+    g = synth.chunglu_graph(2000, 15000, 2.2, 5)
+    kw = dict(k=8, mode=mode, num_layers=3, refresh_fraction=frac, refresh_period=1, rng_seed=5)
+    gs, os_ = gss.Sampler(g.num_nodes, gss.upload_graph(g), tuning=dict(pipeline_depth=1), **kw), oracle_sampler(g, kw)
+    step = 0
+    for fan in ([2], [1, 1, 2], [2, 2], [2, 1, 1]):
+        for batch in (1, 2, 3, 4, 5, 7):
+            seeds = synth.seeds_for_step(2000, batch, 9, step)
+            assert_blocks_equal(gs.step(torch.from_numpy(seeds).cuda(), fan, step), os_.step(seeds, fan, step), ctx=f"{fan} x {batch}")
+            step += 1
+    gs.close(); os_.close()
