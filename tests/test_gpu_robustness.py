@@ -136,3 +136,69 @@ def test_buffers_of_a_few_bytes_grow_by_a_few_bytes(mode, frac, tuning):
             assert_blocks_equal(gs.step(torch.from_numpy(seeds).cuda(), fan, step), os_.step(seeds, fan, step), ctx=f"{fan} x {batch}")
             step += 1
     gs.close(); os_.close()
+
+
+def guarded_allocator(guard=4096):
+    from paper_2406_17918_amd import gss
+
+    class Guarded(gss._TorchAllocator):
+        """Every allocation sits between two guard zones filled with a pattern; check() verifies them."""
+
+        def __init__(self):
+            super().__init__("cuda:0")
+            self.whole = {}
+
+        def _alloc(self, ctx, nbytes):
+            n = int(nbytes)
+            t = self.torch.full((n + 2 * guard,), 0xA5, dtype=self.torch.uint8, device=self.device)
+            p = t.data_ptr() + guard
+            self.whole[p] = t
+            self.live[p] = t[guard:guard + n]
+            return p
+
+        def _free(self, ctx, ptr):
+            self.check(int(ptr))
+            self.whole.pop(int(ptr), None)
+            super()._free(ctx, ptr)
+
+        def check(self, only=None):
+            for p, t in self.whole.items():
+                if only is not None and p != only:
+                    continue
+                n = t.numel() - 2 * guard
+                assert bool((t[:guard] == 0xA5).all()) and bool((t[guard + n:] == 0xA5).all()), f"write outside an allocation of {n} bytes"
+
+    return Guarded()
+
+
+@pytest.mark.parametrize("mode,frac,k,fan,theta", [
+    (gsso.MODE_SHARED_OTF, 0.2, 12, [3, 4, 2], -1), (gsso.MODE_SHARED_OTF, 0.3, 9, [4, 4], 12), (gsso.MODE_OTF, 0.25, 10, [5, 3, 2], -1),
+    (gsso.MODE_FCR, 0.0, 10, [4, 4, 4], -1), (gsso.MODE_FBL, 0.0, 8, [3, 3], -1), (gsso.MODE_OTF, 0.2, 40, [20, 10], -1)])
+def test_no_write_lands_outside_an_allocation(mode, frac, k, fan, theta, tuning):
+    # every buffer the library asks for sits between guard zones; batches of 1 to 600 seeds in random order (buffers of
+    # a few bytes up to many tiles, growing while steps are in flight); the zones are intact after every collected
+    # step and when a buffer is returned, and the blocks equal the oracle's
+    import torch
+    from paper_2406_17918_amd import gss
+    g = synth.chunglu_graph(3000, 30000, 2.2, 21)
+    kw = dict(k=k, mode=mode, num_layers=len(fan), refresh_fraction=frac, refresh_period=2, rng_seed=31, degree_threshold=theta)
+    a = guarded_allocator()
+    gs, os_ = gss.Sampler(g.num_nodes, gss.upload_graph(g), allocator=a, **kw), oracle_sampler(g, kw)
+    rs = np.random.default_rng(7)
+    batches = [int(b) for b in rs.choice([1, 2, 3, 5, 9, 30, 64, 129, 300, 600], size=40)]
+    seeds = [synth.seeds_for_step(3000, b, 4, i) for i, b in enumerate(batches)]
+    dev = [torch.from_numpy(x).cuda() for x in seeds]
+    done = 0
+    for i in range(len(batches)):
+        while i - done >= gs.pipeline_depth:
+            assert_blocks_equal(gs.step_wait(), os_.step(seeds[done], fan, done), ctx=f"step {done}")
+            a.check()
+            done += 1
+        gs.step_async(dev[i], fan, i)
+    while done < len(batches):
+        assert_blocks_equal(gs.step_wait(), os_.step(seeds[done], fan, done), ctx=f"step {done}")
+        done += 1
+    torch.cuda.synchronize()
+    a.check()
+    gs.close(); os_.close()
+    assert not a.whole
