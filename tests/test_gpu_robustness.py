@@ -202,3 +202,36 @@ def test_no_write_lands_outside_an_allocation(mode, frac, k, fan, theta, tuning)
     a.check()
     gs.close(); os_.close()
     assert not a.whole
+
+
+@pytest.mark.parametrize("mode,frac,k,fan,tune", [
+    (gsso.MODE_OTF, 0.2, 25, [25, 20], {}), (gsso.MODE_SHARED_OTF, 0.2, 64, [30, 30], {}), (gsso.MODE_FCR, 0.0, 12, [6, 6], {}),
+    (gsso.MODE_OTF_FETCH, 0.5, 16, [8, 8], {}), (gsso.MODE_OTF_LAYER, 0.25, 16, [8, 4], {}), (gsso.MODE_SHARED_FCR, 0.0, 20, [10, 10], {}),
+    (gsso.MODE_OTF, 0.2, 12, [6, 6], dict(lds_dedupe=1, insert_phase=1)), (gsso.MODE_OTF, 0.2, 12, [6, 6], dict(dedupe_layout=2))])
+def test_no_write_lands_outside_an_allocation_on_a_typed_graph(mode, frac, k, fan, tune, tuning):
+    # the same on a graph with four node types and seven relations (per-type frontiers, per-relation outputs), in the
+    # remaining modes, with the LDS stage of the dedupe and with the hashed table
+    import torch
+    from paper_2406_17918_amd import gss
+    g = synth.hetero_graph([1200, 2000, 60, 300], [(1, 2, 2600), (1, 0, 9000), (0, 0, 5000), (0, 3, 8000)], 2.2, seed=8)
+    kw = dict(k=k, mode=mode, num_layers=len(fan), refresh_fraction=frac, refresh_period=3, rng_seed=13)
+    a = guarded_allocator()
+    gs, os_ = gss.Sampler(g.num_nodes, gss.upload_graph(g), allocator=a, tuning=tune, **kw), oracle_sampler(g, kw)
+    rs = np.random.default_rng(11)
+    batches = [int(b) for b in rs.choice([1, 2, 3, 7, 40, 150, 400], size=24)]
+    seeds = [synth.seeds_for_step(g.num_nodes[0], b, 6, i) for i, b in enumerate(batches)]
+    dev = [torch.from_numpy(x).cuda() for x in seeds]
+    done = 0
+    for i in range(len(batches)):
+        while i - done >= gs.pipeline_depth:
+            assert_blocks_equal(gs.step_wait(), os_.step(seeds[done], fan, done), ctx=f"step {done}")
+            a.check()
+            done += 1
+        gs.step_async(dev[i], fan, i)
+    while done < len(batches):
+        assert_blocks_equal(gs.step_wait(), os_.step(seeds[done], fan, done), ctx=f"step {done}")
+        done += 1
+    torch.cuda.synchronize()
+    a.check()
+    gs.close(); os_.close()
+    assert not a.whole
