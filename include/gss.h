@@ -163,7 +163,7 @@ typedef struct {
                                    2 + depth / period sets (3 at least, 5 at most) when they fit 1/8 of the free device
                                    memory at gss_create, else 3, else 2 (if they fit half of it), else 1.            */
   int32_t pipeline_depth;       /* 1..GSS_MAX_IN_FLIGHT: value of gss_pipeline_depth().  Default 4 L + 2 (twice that
-                                   where a launch starts two steps).  Every step in flight owns scratch, outputs and
+                                   where a launch starts two steps; max(5, L + 2) with visit-once steps).  Every step in flight owns scratch, outputs and
                                    (direct layout) a dedupe table.                                                    */
   int32_t steps_per_tick;       /* 1 | 2: steps a launch starts (2 only in modes that never write a table)           */
   int32_t insert_phase;         /* 1: every hop gets a separate insert phase (visit-once steps: after the place phase,
@@ -204,7 +204,9 @@ gss_status gss_step(gss_sampler* s, const int32_t* seeds, int32_t num_seeds, int
 /* The same step split in two so that the host never idles the GPU between minibatches:
  * gss_step_async validates, plans the step, issues ONE launch (the step's first phase together with the
  * next phase of every older step in flight) and returns at once - in the modes without any refresh (FBL, OTF_FETCH)
- * on graphs with one relation only every second call launches, for the two newest steps together;
+ * on graphs with one relation only every second call launches, for the two newest steps together; in SHARED_OTF,
+ * whose steps are one dependent chain of launches (a step's sample or chain phases must all run before the next
+ * step's first), as many launches as that chain has, so that it never waits for the host;
  * gss_step_wait issues the launches the OLDEST step in flight still needs, blocks until it has finished and
  * fills *out exactly like gss_step.  A step with P phases (3 to 4 per hop) completes after P launches, so a caller
  * that keeps gss_pipeline_depth(s) steps in flight pays one launch (or half a launch) per step.  At most gss_pipeline_depth(s) steps may be in flight (one more gss_step_async returns
