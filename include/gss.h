@@ -182,7 +182,12 @@ typedef struct {
   int32_t lds_dedupe;           /* 1: the insert and place phases first dedupe each tile of 1024 picks in an LDS hash
                                    table and send only the tile's first pick of an id to the global dedupe table.
                                    Default off: measured slower (profiles/lds_dedupe_stage_ab.txt)                     */
-  int32_t reserved[5];          /* must be 0                                                                          */
+  int32_t group_width;          /* lanes per frontier node in the sample phase.  Default: 32 (64 for rows of more than
+                                   32 slots), and on one-relation graphs in FCR / OTF / OTF_LAYER / SHARED_FCR, in
+                                   launches whose sample phases expect 16,384 nodes or more, 21 for rows of 17 to 20
+                                   slots (three nodes per wavefront) and 16 for rows of up to 16 slots (four).
+                                   32: never the narrow groups; 1: the narrow groups in every launch                  */
+  int32_t reserved[4];          /* must be 0                                                                          */
 } gss_tuning;
 
 /* gss_create with the layout choices of `tuning` (NULL: all defaults, which is what gss_create passes). */

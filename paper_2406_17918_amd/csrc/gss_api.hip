@@ -39,6 +39,7 @@ constexpr int TICK_EVENTS = 2 * GSS_MAX_IN_FLIGHT;   // more than the steps that
 constexpr int64_t SAMPLE_WIDE_GROUPS = 4096;      // expected frontier nodes of a hop from which a sample group takes two nodes (several relations)
 constexpr int64_t INSERT_SPLIT_SLOTS = 48 * 1024;   // expected pick slots of a hop from which its inserts get their own phase
 constexpr int64_t TWO_STEP_PICKS = 400 * 1024;    // expected picks of a step up to which two steps share a tick
+constexpr int64_t NARROW_MIN_NODES = 16 * 1024;     // expected frontier nodes of a launch's sample slices from which they take narrow groups
 constexpr int64_t INSERT_SMALL_SLOTS = 16 * 1024;   // ... and up to which they do, too (narrow hops)
 constexpr int DENSE_TICK_WGS = 5000;                // workgroups of a launch from which the kernel's eight-per-CU build is used
 static_assert(GSS_MAX_LAYERS <= SCHED_MAX_LAYERS, "the phase list of a step holds GSS_MAX_LAYERS hops");
@@ -171,6 +172,9 @@ struct gss_sampler {
   int dense_policy = 0;                  // gss_tuning.tick_build - 0: launches of DENSE_TICK_WGS workgroups and more use the dense build; 1: all, 2: none
   uint32_t first_version = VERSION_FIRST;   // where a slot's dedupe-table version counter starts
   int tick_cap = 1;                      // slices one launch can carry
+  int group_w = 32;                      // lanes per frontier node in the sample phase: 64 or 32 ...
+  int narrow_w = 0;                      // ... or, in launches whose sample slices expect many nodes, 21 or 16 (0: never)
+  bool narrow_always = false;            // gss_tuning.group_width = 1: in every launch
   bool lds_stage = false;                // gss_tuning.lds_dedupe: the per-tile LDS stage of the dedupe
   int chain_wg_cap = 4096;               // most workgroups of a chain slice, which stride over the rest (the 4,096-seed workload: 2,048 +5 %, 8,192 +5 %)
   bool visit_once_forced = false;        // gss_tuning.visit_once == 1: also the steps of blocking calls
@@ -328,7 +332,7 @@ SlotConst slot_const(const gss_sampler* s, const Slot& sl) {
 }
 
 // Kernel arguments of item `it` (one phase of one hop) of the step held by `sl`.
-void fill_slice(gss_sampler* s, Slot& sl, int it, HopParams& P) {
+void fill_slice(gss_sampler* s, Slot& sl, int it, HopParams& P, int width) {
   const int T = s->T, R = s->R, L = sl.L, h = sl.items.item_hop[it], l = L - 1 - h;
   memset(static_cast<void*>(&P), 0, sizeof P);
   P.phase = sl.items.item_phase[it];
@@ -400,7 +404,7 @@ void fill_slice(gss_sampler* s, Slot& sl, int it, HopParams& P) {
     // full tick - 16,384-seed steps +9 % with 8,192.  The shared-table refresh mode runs its sample phases nearly
     // alone, one step after the other: there 8,192 are 1.5 % faster)
     const int64_t cap = (s->otf && s->shared) ? 8192 : 2048;
-    const int64_t gpw = s->k > 32 ? 4 : 8;       // groups of a workgroup: 32 lanes per node, or 64 for rows of more than 32 slots
+    const int64_t gpw = 4 * (64 / width);        // groups of a workgroup (four wavefronts): 64 / 32 / 21 / 16 lanes per node
     P.gx = (int32_t)std::min<int64_t>(std::max<int64_t>((want + gpw * per - 1) / (gpw * per), 1), cap);
     P.gy = R;                                    // per relation: a group per frontier node
     P.gxd = (int32_t)((P.gx * gpw + 255) / 256); P.gyd = T;   // per node type: a thread per frontier node
@@ -482,8 +486,24 @@ gss_status tick(gss_sampler* s, int* issued) {
   HopParams* P = s->tick_launch;
   int order[2 * GSS_MAX_IN_FLIGHT];
   const ChainArgs* chain = nullptr;      // of the tick's chain phase (chain phases of different steps never share a tick)
+  // Lanes per frontier node, for all sample slices of the tick: the narrow groups (three or four nodes per wavefront)
+  // where the launch has enough nodes for the vector instructions to be what bounds it; few nodes are bound by their
+  // dependent chains, and fewer, longer-lived wavefronts only lengthen those (the 128-seed workload +4 %, the
+  // 1,024-seed ones -2 .. 0 %, steps of 16,384 seeds and more -8 .. -10 %).
+  int width = s->group_w;
+  if (s->narrow_w) {
+    double nodes = 0.0;
+    for (int i = 0; i < n; ++i)
+      if (pick[i].item >= 0 && take[i]->items.item_phase[pick[i].item] == PH_SAMPLE) {
+        const int h = take[i]->items.item_hop[pick[i].item];
+        double mf = 1.0;
+        for (int t = 0; t < s->T; ++t) mf = std::max(mf, (double)take[i]->fub[h][t]);
+        nodes += std::min(1.0, 1.1 * (double)s->fill_ratio[h]) * mf;
+      }
+    if (s->narrow_always || nodes >= (double)NARROW_MIN_NODES) width = s->narrow_w;
+  }
   for (int i = 0; i < n; ++i) {
-    if (pick[i].item >= 0) fill_slice(s, *take[i], pick[i].item, all[i]);
+    if (pick[i].item >= 0) fill_slice(s, *take[i], pick[i].item, all[i], width);
     else { fill_chain_slice(s, *take[i], -1 - pick[i].item, all[i]); chain = &take[i]->chain_args; }
     order[i] = i;
   }
@@ -512,7 +532,7 @@ gss_status tick(gss_sampler* s, int* issued) {
     // size, 1-4 % per step on the 1,024-seed workload; FBL and OTF fetch, which draw from the adjacency, lose 2-7 %)
     const bool rows_only = s->fcr && !s->shared && s->theta < 0;
     const bool dense = s->dense_policy == 1 || (s->dense_policy == 0 && (rows_only || wgs >= DENSE_TICK_WGS));
-    hipError_t e = launch_tick(P, m, s->relc_h, s->relc_d, s->slotc_d, s->visit_once, chain, s->work, s->timer, last ? done : nullptr, dense);
+    hipError_t e = launch_tick(P, m, s->relc_h, s->relc_d, s->slotc_d, s->visit_once, chain, s->work, s->timer, last ? done : nullptr, dense, width);
     if (e != hipSuccess) { s->poisoned = true; return fail(s, GSS_ERR_DEVICE, "launch: %s", hipGetErrorString(e)); }
   }
   for (int i = 0; i < n; ++i) {
@@ -633,7 +653,7 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   if (tn.dedupe_layout < 0 || tn.dedupe_layout > 2 || tn.table_sets < 0 || tn.table_sets > MAX_TABLE_SETS ||
       tn.pipeline_depth < 0 || tn.pipeline_depth > GSS_MAX_IN_FLIGHT || tn.steps_per_tick < 0 || tn.steps_per_tick > 2 ||
       tn.insert_phase < 0 || tn.insert_phase > 2 || tn.scan_phase < 0 || tn.scan_phase > 1 || tn.tick_build < 0 ||
-      tn.tick_build > 2 || tn.visit_once < 0 || tn.visit_once > 2 || tn.chain_workgroups < 0 || tn.chain_workgroups > 65536 || tn.lds_dedupe < 0 || tn.lds_dedupe > 1 || tn.first_dedupe_version >= VERSION_LAST)
+      tn.tick_build > 2 || tn.visit_once < 0 || tn.visit_once > 2 || tn.chain_workgroups < 0 || tn.chain_workgroups > 65536 || tn.lds_dedupe < 0 || tn.lds_dedupe > 1 || (tn.group_width != 0 && tn.group_width != 1 && tn.group_width != 32) || tn.first_dedupe_version >= VERSION_LAST)
     return early(GSS_ERR_INVALID_ARG, "invalid argument (tuning field out of range)");
   for (int32_t v : tn.reserved)
     if (v != 0) return early(GSS_ERR_INVALID_ARG, "invalid argument (tuning: reserved fields must be 0)");
@@ -721,6 +741,18 @@ gss_status gss_create_tuned(const gss_graph* g, const gss_config* c, const gss_t
   s->steps_per_tick = (!s->otf && !s->fcr && s->R == 1 && s->T == 1 && s->k <= 32) ? 2 : 1;
   if (tn.steps_per_tick) s->steps_per_tick = (!s->otf && s->k <= 32 && tn.steps_per_tick == 2) ? 2 : 1;
   if (s->lds_stage) s->steps_per_tick = 1;
+  // Lanes per frontier node in the sample phase.  A row of k slots keeps k lanes busy, and a wavefront's vector
+  // instructions cost the same however many of its lanes take part: rows of up to 20 slots can get 21 lanes (three
+  // nodes per wavefront), of up to 16 slots 16 lanes (four), instead of 32 (two) - chosen per launch, see tick().
+  // One-relation graphs, the modes with cached rows and one step per launch (these builds exist for the plain launch
+  // of up to 12 slices only).
+  s->group_w = s->k > 32 ? 64 : 32;
+  const bool rows_mode = c->mode == GSS_MODE_FCR || c->mode == GSS_MODE_OTF || c->mode == GSS_MODE_OTF_LAYER || c->mode == GSS_MODE_SHARED_FCR;
+  if (s->k <= 20 && s->R == 1 && s->T == 1 && rows_mode && s->steps_per_tick == 1 && !s->lds_stage && !s->visit_once && tn.group_width != 32) {
+    s->narrow_w = s->k <= 16 ? 16 : 21;
+    s->narrow_always = tn.group_width == 1;
+    s->tick_cap = std::min(s->tick_cap, 12);
+  }
   // A step of L hops has up to 4 L phases, one per launch: with two more steps than that in flight the step a
   // caller waits for has left the queue before.  (Deeper rings only widen the memory the launches touch: every slot
   // has scratch and a dedupe table of its own - 4 L + 4 was 1 % slower on the 1,024-seed workloads, 4 L too shallow.)

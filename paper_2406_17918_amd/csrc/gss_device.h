@@ -256,9 +256,12 @@ hipError_t launch_list_from_map(const int32_t* map, int64_t n, int32_t* list, hi
 // that fits eight workgroups on a CU instead of seven (for launches of several times the chip's capacity; the compact
 // launch of one-relation graphs has no such build).  `chain_build`: the sampler runs visit-once steps (one relation; at
 // most CHAIN_TICK_SLICES slices per launch); `chain`: the arguments of the launch's chain slice, if it has one.
+// `width`: lanes per frontier node in the sample phase - 64 for rows of more than 32 slots, 32, or (one-relation graphs,
+// at most 12 slices, no chain, no LDS stage) 21 / 16 for rows of up to 20 / 16 slots; the grids of the sample slices must
+// have been sized for it (256 / 64 * (64 / width) nodes per workgroup).
 hipError_t launch_tick(const HopParams* slices, int n, const RelConst* relc_host, const RelConst* relc_dev,
                        const SlotConst* slots_dev, bool chain_build, const ChainArgs* chain, hipStream_t st, LaunchTimer* timer,
-                       hipEvent_t done, bool dense);
+                       hipEvent_t done, bool dense, int width);
 hipError_t launch_validate_graph(const void* indptr, int is64, int64_t n_dst, const int32_t* indices, int64_t nnz,
                                  int64_t n_src, int32_t* state, hipStream_t st);
 hipError_t launch_cache_read(const int32_t* table, const int32_t* row_of, int64_t n, int k, int S, int32_t* out,

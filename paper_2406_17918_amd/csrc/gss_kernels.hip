@@ -105,22 +105,38 @@ __device__ __forceinline__ int mask_ffs(uint64_t m) { return __ffsll((unsigned l
 template <int W>
 struct GrpT {
   static constexpr int WIDTH = W;
-  static constexpr int LOG2_WIDTH = W == 64 ? 6 : 5;
+  static constexpr int PER_WAVE = 64 / W;               // groups of a wavefront (W = 21: three, and lane 63 has no group)
+  static constexpr int PER_WG = (TILE_THREADS / 64) * PER_WAVE;   // groups of a workgroup
+  static constexpr bool POW2 = (W & (W - 1)) == 0;
+  static constexpr int LOG2_WIDTH = W == 64 ? 6 : (W == 32 ? 5 : (W == 16 ? 4 : (W == 8 ? 3 : 0)));
   using Mask = MaskT<W>;
   // LDS address space made explicit: volatile accesses through a generic pointer would be emitted as
   // flat memory instructions instead of ds_read / ds_write.
   typedef __attribute__((address_space(3))) volatile GroupLdsT<W>* LdsPtr;
   int sub;                 // lane within the group
-  int half;                // group within the wavefront (W = 32)
+  int half;                // group within the wavefront
+  bool idle;               // a lane beyond the wavefront's last group (only when W does not divide 64): it takes no part
   LdsPtr L;
   __device__ __forceinline__ void init(GroupLdsT<W>* lds) {        // `lds`: one scratch per group of the workgroup
-    sub = (int)(threadIdx.x & (unsigned)(W - 1));
-    half = W == 32 ? (int)((threadIdx.x >> 5) & 1u) : 0;
-    L = (LdsPtr)&lds[threadIdx.x / (unsigned)W];
+    if constexpr (W == 32 || W == 64) {
+      sub = (int)(threadIdx.x & (unsigned)(W - 1));
+      half = W == 32 ? (int)((threadIdx.x >> 5) & 1u) : 0;
+      idle = false;
+      L = (LdsPtr)&lds[threadIdx.x / (unsigned)W];
+    } else {
+      const int lane = (int)(threadIdx.x & 63u);
+      half = lane / W;
+      idle = half >= PER_WAVE;
+      if (idle) half = PER_WAVE - 1;
+      sub = lane - half * W;
+      L = (LdsPtr)&lds[(int)(threadIdx.x >> 6) * PER_WAVE + half];
+    }
   }
+  __device__ __forceinline__ int index_in_workgroup() const { return (int)(threadIdx.x >> 6) * PER_WAVE + half; }
   __device__ __forceinline__ Mask below() const { return ((Mask)1 << sub) - (Mask)1; }          // the lanes before this one
   __device__ __forceinline__ bool in(Mask m) const { return ((m >> sub) & (Mask)1) != 0; }       // is this lane's bit set
-  __device__ __forceinline__ static Mask first(int n) { return n >= W ? ~(Mask)0 : (((Mask)1 << n) - (Mask)1); }
+  __device__ __forceinline__ static Mask all() { return (W == 64 || W == 32) ? ~(Mask)0 : (Mask)(((Mask)1 << (W & 31)) - (Mask)1); }
+  __device__ __forceinline__ static Mask first(int n) { return n >= W ? all() : (((Mask)1 << n) - (Mask)1); }
 };
 using GroupLds = GroupLdsT<32>;
 using Grp = GrpT<32>;
@@ -129,7 +145,8 @@ template <int W>
 __device__ __forceinline__ MaskT<W> grp_ballot(const GrpT<W>& G, bool pred) {
   const uint64_t b = __ballot(pred);
   if constexpr (W == 64) return b;
-  else return G.half ? (uint32_t)(b >> 32) : (uint32_t)b;
+  else if constexpr (W == 32) return G.half ? (uint32_t)(b >> 32) : (uint32_t)b;
+  else return (uint32_t)(b >> (G.half * W)) & GrpT<W>::all();
 }
 __device__ __forceinline__ uint32_t below_mask(int sub) { return (1u << sub) - 1u; }
 
@@ -187,7 +204,7 @@ __device__ __forceinline__ int grp_rejection_fill(const GrpT<W>& G, MaskT<W> pen
       break;
     }
     const int np = mask_popc(pend);
-    if (!FEW && np <= 8 && a + (uint32_t)GRP <= 65536u) {
+    if (GrpT<W>::POW2 && !FEW && np <= 8 && a + (uint32_t)GRP <= 65536u) {   // (the lane -> (slot, round) split below wants a power of two)
       // Few slots pending: a round would run the whole Philox block and a trip to the adjacency for a handful of
       // lanes.  Instead the 32 lanes compute the proposals of A = 16 / 8 / 4 consecutive rounds at once (lane ->
       // (pending slot q, round t); a proposal is a pure function of slot and round), and the rounds are then
@@ -320,6 +337,15 @@ __device__ __forceinline__ int grp_refresh_part(const GrpT<W>& G, int val, int k
     const uint32_t lo = (uint32_t)wave_low, hi = (uint32_t)(wave_low >> 32);
     enough = (__popc(lo) >= n_new || !(wave_here & 1ull)) && (__popc(hi) >= n_new || !((wave_here >> 32) & 1ull));
     scan = lo | hi;
+  } else if constexpr (W < 32) {
+    enough = true;
+    scan = 0ull;
+#pragma unroll
+    for (int q = 0; q < GrpT<W>::PER_WAVE; ++q) {
+      const uint32_t m = (uint32_t)(wave_low >> (q * W)) & GrpT<W>::all();
+      enough = enough && (__popc(m) >= n_new || !((wave_here >> (q * W)) & 1ull));
+      scan |= m;
+    }
   }
   int er;
   if (enough) {
@@ -620,15 +646,16 @@ __device__ __forceinline__ void sample_phase(const HP& P, const Wg wg, GroupLdsT
   constexpr int GRP = W;
   GrpT<W> G;
   G.init(lds);
+  if (G.idle) return;                 // (no barrier below: the phase is a per-group loop)
   const int r = wg.y;
   const RelParam& RP = rel_of(P, r);
   const RelConst& RC = P.rc(r);
-  const int grp = wg.x * (int)(blockDim.x / W) + (int)(threadIdx.x / W);
+  const int grp = wg.x * GrpT<W>::PER_WG + G.index_in_workgroup();
   // the first node id is loaded before the frontier size is known (both loads travel together);
   // `frontier_cap` is the allocated length of the frontier array
   const int v_first = (grp < type_of(P, RP.dst_type).frontier_cap) ? type_of(P, RP.dst_type).frontier[grp] : 0;
   const int F = frontier_count(P, RP.dst_type);
-  const int ngrp = P.gx * (int)(blockDim.x / W);
+  const int ngrp = P.gx * GrpT<W>::PER_WG;
   const int k = P.k, f = P.f, sub = G.sub;
   const int32_t* __restrict__ frontier = type_of(P, RP.dst_type).frontier;
   const uint32_t src_key_off = type_of(P, RP.src_type).key_off;
@@ -1357,7 +1384,7 @@ __device__ __forceinline__ void emit_phase(const HP& P, const Wg wg, EmitLds* L,
 // ------------------------------------------------------------------------------------------
 template <int W>
 union TickLds {
-  GroupLdsT<W> group[256 / W];
+  GroupLdsT<W> group[GrpT<W>::PER_WG];
   int scan[32];
   EmitLds emit;
 };
@@ -1417,9 +1444,9 @@ __device__ __forceinline__ void tick_body(const TP& M_by_value) {
 // chains of a few narrow slices, lose 3-6 % on the workloads with a refresh in the sample phase.
 template <class TP, int W>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96))) void step_tick_kernel(TP M) { tick_body<TP, W>(M); }
-template <class TP>
+template <class TP, int W = 32>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_num_sgpr(96), amdgpu_waves_per_eu(8, 8))) void step_tick_dense_kernel(TP M) {
-  tick_body<TP, 32, true>(M);
+  tick_body<TP, W, true>(M);
 }
 // The compact form for one-relation graphs: the slice's full arguments are put together from the launch's shared
 // part, the slice's own part and the slot's entry of the device table (one more scalar load at the start).
@@ -1681,7 +1708,8 @@ int tick_capacity(int R, int T) {
 
 template <class HP, int D>
 static hipError_t launch_tick_t(const HopParams* P, int n, const RelConst* relc_host, const RelConst* relc_dev,
-                                const ChainArgs* chain, hipStream_t st, LaunchTimer* timer, hipEvent_t done, bool dense) {
+                                const ChainArgs* chain, hipStream_t st, LaunchTimer* timer, hipEvent_t done, bool dense,
+                                int width = 0) {
   using TP = TickT<HP, D>;
   static_assert(sizeof(TP) <= 4000, "kernel arguments are limited to 4 KB");
   TP M;
@@ -1701,13 +1729,24 @@ static hipError_t launch_tick_t(const HopParams* P, int n, const RelConst* relc_
     M.end[i] = total;
   }
   hipEvent_t start = nullptr, stop = nullptr;
-  // rows of more than 32 slots: the build with one node per wavefront (it has no dense variant, and no chain code)
+  // rows of more than 32 slots: the build with one node per wavefront (it has no dense variant, and no chain code);
+  // rows of up to 20 / 16 slots on one-relation graphs: the builds with three / four nodes per wavefront
   const bool wide = P[0].k > 32;
   void (*kernel)(TP) = dense ? step_tick_dense_kernel<TP> : step_tick_kernel<TP, 32>;
   if constexpr (TP::HAS_CHAIN) {
-    if (wide) return hipErrorInvalidValue;
+    if (wide || (width != 0 && width != 32)) return hipErrorInvalidValue;
   } else if (wide) {
+    if (width != 0 && width != 64) return hipErrorInvalidValue;
     kernel = step_tick_kernel<TP, 64>;
+  } else if (width == 21 || width == 16) {
+    if constexpr (std::is_same<HP, HopParamsMono>::value) {
+      if (width == 21) kernel = dense ? step_tick_dense_kernel<TP, 21> : step_tick_kernel<TP, 21>;
+      else kernel = dense ? step_tick_dense_kernel<TP, 16> : step_tick_kernel<TP, 16>;
+    } else {
+      return hipErrorInvalidValue;
+    }
+  } else if (width != 0 && width != 32) {
+    return hipErrorInvalidValue;
   }
   if (timer && timer->bracket(KID_STEP_TICK, &start, &stop))
     hipExtLaunchKernelGGL(kernel, dim3((unsigned)total), dim3(256), 0, st, start, stop, 0, M);
@@ -1770,7 +1809,7 @@ static hipError_t launch_tick_mono(const HopParams* P, int n, const RelConst* re
 
 hipError_t launch_tick(const HopParams* P, int n, const RelConst* relc_host, const RelConst* relc_dev,
                        const SlotConst* slots_dev, bool chain_build, const ChainArgs* chain, hipStream_t st, LaunchTimer* timer,
-                       hipEvent_t done, bool dense) {
+                       hipEvent_t done, bool dense, int width) {
   if (n < 1 || n > tick_capacity(P[0].R, P[0].T)) return hipErrorInvalidValue;
   const int R = P[0].R, T = P[0].T;
   if (chain_build) {
@@ -1784,15 +1823,18 @@ hipError_t launch_tick(const HopParams* P, int n, const RelConst* relc_host, con
     if (R != 1 || T != 1 || n > 12 || P[0].k > 32) return hipErrorInvalidValue;
     return launch_tick_t<HopParamsStaged, 12>(P, n, relc_host, relc_dev, nullptr, st, timer, done, dense);
   }
+  const bool narrow = width == 21 || width == 16;
+  if (narrow && (chain_build || (P[0].insert_split & 2) || R != 1 || T != 1 || n > 12)) return hipErrorInvalidValue;
   if (R == 1 && T == 1 && n > 12) {
     if (!slots_dev || P[0].k > 32) return hipErrorInvalidValue;   // (the compact form has no build for wide rows)
     return launch_tick_mono(P, n, relc_host, slots_dev, st, timer, done);
   }
   if (R == 1 && T == 1) {
-    if (n == 1) return launch_tick_t<HopParamsMono, 1>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
-    if (n <= 4) return launch_tick_t<HopParamsMono, 4>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
-    if (n <= 8) return launch_tick_t<HopParamsMono, 8>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
-    return launch_tick_t<HopParamsMono, 12>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);
+    // (the one-slice builds with narrow groups would spill vector registers when held to 64 of them)
+    if (n == 1) return launch_tick_t<HopParamsMono, 1>(P, n, relc_host, relc_dev, chain, st, timer, done, dense && !narrow, width);
+    if (n <= 4) return launch_tick_t<HopParamsMono, 4>(P, n, relc_host, relc_dev, chain, st, timer, done, dense, width);
+    if (n <= 8) return launch_tick_t<HopParamsMono, 8>(P, n, relc_host, relc_dev, chain, st, timer, done, dense, width);
+    return launch_tick_t<HopParamsMono, 12>(P, n, relc_host, relc_dev, chain, st, timer, done, dense, width);
   }
   if (R <= HopParamsSmall::MAX_R && T <= HopParamsSmall::MAX_T) {
     if (n == 1) return launch_tick_t<HopParamsSmall, 1>(P, n, relc_host, relc_dev, chain, st, timer, done, dense);

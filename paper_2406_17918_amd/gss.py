@@ -54,7 +54,8 @@ class gss_tuning(C.Structure):
     _fields_ = [("dedupe_layout", C.c_int32), ("table_sets", C.c_int32), ("pipeline_depth", C.c_int32),
                 ("steps_per_tick", C.c_int32), ("insert_phase", C.c_int32), ("scan_phase", C.c_int32),
                 ("tick_build", C.c_int32), ("first_dedupe_version", C.c_uint32), ("visit_once", C.c_int32),
-                ("chain_workgroups", C.c_int32), ("lds_dedupe", C.c_int32), ("reserved", C.c_int32 * 5)]
+                ("chain_workgroups", C.c_int32), ("lds_dedupe", C.c_int32), ("group_width", C.c_int32),
+                ("reserved", C.c_int32 * 4)]
 
 
 class gss_block_nodes(C.Structure):

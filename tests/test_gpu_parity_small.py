@@ -584,3 +584,52 @@ def test_parity_with_the_lds_stage_of_the_dedupe(k, mode, frac, period, fanouts,
     gt = synth.hetero_graph([1200, 2000, 60, 300], [(1, 2, 2600), (1, 0, 9000), (0, 0, 5000), (0, 3, 8000)], 2.2, seed=8)
     if mode in (OTF, FCR) and len(fanouts) == 2:
         assert run_parity_pipelined(gt, kw, fanouts, 100, steps=range(8)) > 0
+
+
+NARROW_CASES = [c for c in CASES if c[0] <= 20 and c[1] in (FCR, OTF, OTF_LAYER, SHARED_FCR)] + [
+    # k, mode, fraction, period, fanouts, batch: rows of 17 .. 20 slots take 21 lanes, up to 16 slots 16 lanes
+    (20, OTF, 1.0, 1, [20, 20], 333), (19, OTF, 0.3, 2, [7, 19, 2], 190), (18, FCR, 0.0, 2, [18, 9], 400),
+    (17, OTF_LAYER, 0.4, 2, [5, 17], 260), (16, FCR, 0.0, 1, [16, 16], 130), (13, OTF, 0.25, 1, [13, 2, 6], 210),
+    (9, OTF, 0.5, 1, [9, 9, 9], 64), (3, OTF, 0.4, 1, [3, 2], 900), (2, SHARED_FCR, 0.0, 3, [1, 1], 500),
+    (20, SHARED_FCR, 0.0, 2, [10, 6, 4], 150),
+]
+
+
+@pytest.mark.parametrize("k,mode,frac,period,fanouts,batch", NARROW_CASES)
+def test_parity_with_three_or_four_nodes_per_wavefront(k, mode, frac, period, fanouts, batch, tuning):
+    # the sample phase with 21 or 16 lanes per frontier node in every launch (the library's own choice only for
+    # launches with 16,384 nodes and more): blocking and pipelined, with and without the degree split
+    tuning(group_width=1)
+    g = graph_small()
+    kw = dict(k=k, mode=mode, num_layers=len(fanouts), refresh_fraction=frac, refresh_period=period, rng_seed=60221023)
+    assert run_parity(g, kw, fanouts, batch, steps=[0, 1, 2, 3, 5, 6, 9]) > 0
+    assert run_parity_pipelined(g, kw, fanouts, batch, steps=range(22)) > 0
+    if mode in (OTF, FCR):
+        kw["degree_threshold"] = k
+        assert run_parity_pipelined(g, kw, fanouts, batch, steps=range(12)) > 0
+
+
+def test_narrow_groups_on_a_graph_with_hubs_and_at_a_large_batch(tuning):
+    # a star, a clique (k < deg < 2k) and isolated nodes with narrow groups; then a batch large enough for the library
+    # to choose them by itself (its launches mix both widths while the pipeline fills)
+    n = 600
+    rows, cols = [], []
+    for v in range(1, n - 100):
+        rows += [0, v]; cols += [v, 0]
+    for a in range(400, 430):
+        for b in range(a + 1, 430):
+            rows += [a, b]; cols += [b, a]
+    order = np.lexsort((cols, rows))
+    r_, c_ = np.asarray(rows)[order], np.asarray(cols)[order]
+    keep = np.ones(len(r_), bool); keep[1:] = (r_[1:] != r_[:-1]) | (c_[1:] != c_[:-1])
+    r_, c_ = r_[keep], c_[keep]
+    indptr = np.zeros(n + 1, np.int32); np.add.at(indptr, r_ + 1, 1); indptr = np.cumsum(indptr).astype(np.int32)
+    g = synth.Graph([n], [synth.Relation(0, 0, indptr, c_.astype(np.int32))])
+    tuning(group_width=1)
+    for k, frac in ((20, 0.25), (16, 0.5)):
+        kw = dict(k=k, mode=OTF, num_layers=2, refresh_fraction=frac, refresh_period=1, rng_seed=99)
+        assert run_parity(g, kw, [k, 5], 300, steps=range(6)) > 0
+    tuning()
+    big = graph_small(n=60000, m=900000, seed=5)
+    kw = dict(k=20, mode=OTF, num_layers=2, refresh_fraction=0.2, refresh_period=1, rng_seed=7)
+    assert run_parity_pipelined(big, kw, [10, 5], 20000, steps=range(10)) > 0
